@@ -1,0 +1,174 @@
+"""CPU oracle for the SDPA forward pass.  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this module; the product path never does, and the two share no code.
+
+Three independent float64 routines live here:
+
+* :func:`sdpa` -- ctypes front end of ``sdpa_oracle.c`` (plain C + OpenMP), the
+  materialised row-by-row definition of the paper's Eq. 1 (Section 3.1) with
+  M = 0 and the final division of Section 4.1.2.  This is *the* oracle used for
+  parity at every size (it can evaluate a subset of query rows).
+* :func:`sdpa_numpy` -- the same definition as three numpy matrix expressions,
+  for small shapes; kept because it can be checked against Eq. 1 by eye.
+* :func:`sdpa_online` -- the blockwise recurrence of Section 4.1.2 (Eqs. 2-4)
+  taken step by step in float64 with arbitrary tile boundaries.  It exists to
+  show that the recurrence reaches the materialised result (merge identity).
+
+Inputs are numpy arrays holding FP16/BF16-rounded values (Section 4.1.3); they
+are converted to float32 (exact for 16-bit floats) for the C routine, which
+promotes every operand to double.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "sdpa_oracle.c"
+_LIB = _HERE / "libsdpa_oracle.so"
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile ``sdpa_oracle.c`` with gcc (no fast-math: IEEE double throughout)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        cmd = ["gcc", "-O2", "-fopenmp", "-fno-fast-math", "-shared", "-fPIC",
+               str(_SRC), "-o", str(tmp), "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        lib.sdpa_oracle_rows.restype = ctypes.c_int
+        lib.sdpa_oracle_rows.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_void_p, ctypes.c_long,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.sdpa_oracle_num_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    """OpenMP threads the C oracle will use."""
+    return int(_load().sdpa_oracle_num_threads())
+
+
+def _as_f32(x) -> np.ndarray:
+    a = np.asarray(x)
+    if a.dtype not in (np.float16, np.float32, np.float64):
+        raise TypeError(f"unsupported dtype {a.dtype}")
+    a32 = np.ascontiguousarray(a, dtype=np.float32)
+    if a.dtype == np.float64 and not np.array_equal(a32.astype(np.float64), a):
+        raise ValueError("float64 input is not exactly representable in float32")
+    return a32
+
+
+def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False):
+    """Materialised float64 attention, Eq. 1 (Section 3.1) with M = 0.
+
+    q, k, v: arrays of shape [..., S, D] (leading dims are batch/head and must
+    agree).  scale: defaults to 1/sqrt(D) (Section 4.2.1); if given it is used
+    as the float32 value the device receives, promoted to double.
+    rows: optional 1-D sequence of query-row indices evaluated for every
+    batch/head.  Returns o [..., nrows, D] float64 (and lse [..., nrows],
+    p [..., nrows, S] on request).
+    """
+    q32, k32, v32 = _as_f32(q), _as_f32(k), _as_f32(v)
+    if q32.shape != k32.shape or q32.shape != v32.shape or q32.ndim < 2:
+        raise ValueError("q, k, v must have identical shape [..., S, D]")
+    lead, (S, D) = q32.shape[:-2], q32.shape[-2:]
+    BH = int(np.prod(lead, dtype=np.int64)) if lead else 1
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    scale = float(np.float32(scale))
+    if rows is None:
+        rows_arr, nrows, rows_ptr = None, S, None
+    else:
+        rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
+        if rows_arr.ndim != 1:
+            raise ValueError("rows must be one-dimensional")
+        nrows, rows_ptr = rows_arr.size, rows_arr.ctypes.data
+    o = np.empty((BH, nrows, D), dtype=np.float64)
+    lse = np.empty((BH, nrows), dtype=np.float64) if return_lse else None
+    p = np.empty((BH, nrows, S), dtype=np.float64) if return_p else None
+    rc = _load().sdpa_oracle_rows(
+        q32.ctypes.data, k32.ctypes.data, v32.ctypes.data, BH, S, D, scale,
+        rows_ptr, nrows, o.ctypes.data,
+        lse.ctypes.data if lse is not None else None,
+        p.ctypes.data if p is not None else None)
+    if rc != 0:
+        raise RuntimeError(f"sdpa_oracle_rows failed with status {rc}")
+    out = [o.reshape(*lead, nrows, D)]
+    if return_lse:
+        out.append(lse.reshape(*lead, nrows))
+    if return_p:
+        out.append(p.reshape(*lead, nrows, S))
+    return out[0] if len(out) == 1 else tuple(out)
+
+
+def sdpa_numpy(q, k, v, scale=None, return_lse=False):
+    """Eq. 1 (Section 3.1), M = 0, as numpy float64 matrix expressions."""
+    q64 = np.asarray(q, dtype=np.float64)
+    k64 = np.asarray(k, dtype=np.float64)
+    v64 = np.asarray(v, dtype=np.float64)
+    D = q64.shape[-1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    scale = float(np.float32(scale))
+    s = scale * (q64 @ np.swapaxes(k64, -1, -2))
+    m = s.max(axis=-1, keepdims=True)
+    e = np.exp(s - m)
+    L = e.sum(axis=-1, keepdims=True)
+    o = (e @ v64) / L
+    if return_lse:
+        return o, (m + np.log(L))[..., 0]
+    return o
+
+
+def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False):
+    """Blockwise online-softmax attention, Section 4.1.2 (Eqs. 2-4), in float64.
+
+    One [S, D] problem.  ``tile_bounds`` is an increasing list of key indices
+    0 = b_0 < b_1 < ... < b_T = S; tile t holds keys b_t .. b_{t+1}-1.  For each
+    tile, in the paper's order: scores, running max (Eq. 2), normaliser (Eq. 3),
+    output accumulator (Eq. 4); after the last tile O_i = o_i / l_i.  The state
+    starts at m = -inf, l = 0, o = 0 (the paper does not state the start; any
+    start with l = 0, o = 0 and m below every score gives the same result).
+    """
+    q64 = np.asarray(q, dtype=np.float64)
+    k64 = np.asarray(k, dtype=np.float64)
+    v64 = np.asarray(v, dtype=np.float64)
+    S, D = q64.shape
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    scale = float(np.float32(scale))
+    if tile_bounds is None:
+        tile_bounds = [0, S]
+    m = np.full(S, -np.inf)
+    l = np.zeros(S)
+    o = np.zeros((S, D))
+    for lo, hi in zip(tile_bounds[:-1], tile_bounds[1:]):
+        s_tile = scale * (q64 @ k64[lo:hi].T)                    # S_ij for this tile
+        m_old = m
+        m = np.maximum(m_old, s_tile.max(axis=1))                # Eq. 2
+        alpha = np.exp(m_old - m)                                # e^{m_old - m}
+        e = np.exp(s_tile - m[:, None])
+        l = l * alpha + e.sum(axis=1)                            # Eq. 3
+        o = o * alpha[:, None] + e @ v64[lo:hi]                  # Eq. 4
+    out = o / l[:, None]
+    if return_lse:
+        return out, m + np.log(l)
+    return out

@@ -1,0 +1,10 @@
+"""MI355X-native tiled SDPA forward (online softmax, streamed K/V tiles).
+
+The compute path is the HIP library ``libtiled_sdpa.so`` built from ``csrc/``;
+:mod:`.binding` marshals torch tensors to its C-ABI.  :mod:`.workloads` only
+draws seeded inputs.
+"""
+from .binding import (  # noqa: F401
+    F16, BF16, TiledSdpaError, library_path, load_library, sdpa,
+    status_string, tiled_sdpa_fwd, tiled_sdpa_fwd_ex, version,
+)
