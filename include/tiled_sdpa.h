@@ -1,0 +1,92 @@
+/*
+ * tiled_sdpa.h -- C-ABI of the MI355X (gfx950) tiled scaled-dot-product-attention
+ * forward library.
+ *
+ * The operation is the paper's Eq. 1 (Section 3.1) with no mask,
+ *
+ *     O = softmax(Q K^T * scale) V        per (batch, head),
+ *
+ * evaluated blockwise with the online-softmax recurrence of Section 4.1.2
+ * (Eqs. 2-4: running row maximum m, normaliser l and accumulator o over streamed
+ * K/V tiles, final O_i = o_i / l_i), so the S x S score matrix never exists in
+ * memory.  Numerics follow Section 4.1.3: FP16 or BF16 inputs and output, FP32
+ * accumulation of the dot products, the softmax statistics and the output.
+ * The call surface mirrors the functional API of Section 4.2.1,
+ * sdpa(q, k, v, causal, scale) -> o, restricted to causal = false.
+ *
+ * All pointers are DEVICE pointers owned by the caller.  The library allocates
+ * and frees nothing, keeps no state besides its kernel table, never
+ * synchronises, and is thread-safe.  Work is enqueued on `stream`.
+ */
+#ifndef TILED_SDPA_H
+#define TILED_SDPA_H
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* element types (Section 4.1.3) */
+enum { TSDPA_F16 = 0, TSDPA_BF16 = 1 };
+
+/* status codes: every entry point returns one of these and never throws or aborts */
+enum {
+    TSDPA_OK = 0,
+    TSDPA_ERR_NULL_PTR = 1,      /* q, k, v or o is NULL while B*H*S > 0                    */
+    TSDPA_ERR_BAD_SHAPE = 2,     /* negative B, H or S, or B*H*ceil(S/tile_m) overflows int */
+    TSDPA_ERR_BAD_DTYPE = 3,     /* dtype is neither TSDPA_F16 nor TSDPA_BF16               */
+    TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64 or 128                                      */
+    TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
+    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}          */
+    TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
+    TSDPA_ERR_LAUNCH = 8         /* the HIP runtime refused the launch                      */
+};
+
+/* flags for tiled_sdpa_fwd_ex */
+enum {
+    TSDPA_FLAG_LINEAR_GRID = 1u  /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
+};
+
+/*
+ * Forward pass, Eq. 1 via Eqs. 2-4.
+ *
+ *   q, k, v : [B, H, S, D] contiguous row-major, element type `dtype`, device memory,
+ *             16-byte aligned (Section 4.1.1 layout; viewed as [B*H, S, D] and tiled along S).
+ *   o       : [B, H, S, D], same type; every element is overwritten.  Must not alias q, k, v.
+ *   lse     : optional (NULL to skip) FP32 [B, H, S]; receives m_i + ln(l_i), the natural-log
+ *             normaliser of row i, which is what merging partial results over key ranges needs.
+ *   S       : any length >= 0; key columns beyond S contribute nothing and rows beyond S are
+ *             neither computed into memory nor read past the tensor end.
+ *   D       : 64 or 128.
+ *   scale   : multiplies Q K^T; any finite value.  NaN selects the default 1/sqrt(D)
+ *             (Section 4.2.1), since C has no default arguments.
+ *   stream  : hipStream_t (NULL = default stream).  The call returns once the kernel is enqueued.
+ *
+ * Validation order: dtype, D, shape, empty problem (B*H*S == 0 returns TSDPA_OK without
+ * touching memory), null pointers, alignment, tile, scale, launch.
+ */
+int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
+                   int B, int H, int S, int D, float scale, int dtype, void *stream);
+
+/*
+ * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
+ * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
+ * {32,64,128}; tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
+ * tiled_sdpa_fwd uses.  The result does not depend on the tile choice beyond rounding order.
+ */
+int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
+                      int B, int H, int S, int D, float scale, int dtype, void *stream,
+                      int tile_m, int tile_n, unsigned flags);
+
+/* The (tile_m, tile_n) the heuristic picks for a shape; returns a status code. */
+int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, int *tile_m, int *tile_n);
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char *tiled_sdpa_status_string(int status);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int tiled_sdpa_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TILED_SDPA_H */

@@ -1,0 +1,134 @@
+"""ctypes binding of libtiled_sdpa.so: argument marshalling only.
+
+Every step of the forward pass runs in the HIP kernels behind the C-ABI declared
+in include/tiled_sdpa.h.  PyTorch supplies device memory and the current stream.
+There is no CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+from pathlib import Path
+
+F16, BF16 = 0, 1
+FLAG_LINEAR_GRID = 1
+
+_PKG = Path(__file__).resolve().parent
+_LIB_PATH = _PKG / "libtiled_sdpa.so"
+_lib = None
+
+EXPORTS = (
+    "tiled_sdpa_fwd",
+    "tiled_sdpa_fwd_ex",
+    "tiled_sdpa_default_tile",
+    "tiled_sdpa_status_string",
+    "tiled_sdpa_version",
+)
+
+
+class TiledSdpaError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"tiled_sdpa status {status}: {text}")
+        self.status = status
+
+
+def library_path() -> Path:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the HIP library; raises if it has not been built (python -m paper_2603_01960_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not _LIB_PATH.exists():
+        raise FileNotFoundError(
+            f"{_LIB_PATH} not found: build it with `python -m paper_2603_01960_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(str(_LIB_PATH))
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    lib.tiled_sdpa_fwd.restype = ci
+    lib.tiled_sdpa_fwd.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp]
+    lib.tiled_sdpa_fwd_ex.restype = ci
+    lib.tiled_sdpa_fwd_ex.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint]
+    lib.tiled_sdpa_default_tile.restype = ci
+    lib.tiled_sdpa_default_tile.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.tiled_sdpa_status_string.restype = ctypes.c_char_p
+    lib.tiled_sdpa_status_string.argtypes = [ci]
+    lib.tiled_sdpa_version.restype = ci
+    lib.tiled_sdpa_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def version() -> int:
+    return int(load_library().tiled_sdpa_version())
+
+
+def status_string(status: int) -> str:
+    return load_library().tiled_sdpa_status_string(int(status)).decode()
+
+
+def default_tile(B: int, H: int, S: int, D: int, dtype: int):
+    tm, tn = ctypes.c_int(0), ctypes.c_int(0)
+    st = load_library().tiled_sdpa_default_tile(B, H, S, D, dtype, ctypes.byref(tm), ctypes.byref(tn))
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return tm.value, tn.value
+
+
+def tiled_sdpa_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype, stream) -> int:
+    """Raw call: integer device addresses in, status code out (same argument order as the C-ABI)."""
+    return int(load_library().tiled_sdpa_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D,
+                                             float(scale), dtype, stream))
+
+
+def tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype, stream,
+                      tile_m=0, tile_n=0, flags=0) -> int:
+    return int(load_library().tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D,
+                                                float(scale), dtype, stream, tile_m, tile_n, flags))
+
+
+def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False, out=None,
+         lse_out=None, tile=None, flags: int = 0):
+    """o = softmax(q k^T * scale) v for contiguous [B, H, S, D] FP16/BF16 device tensors.
+
+    Mirrors the functional API of Section 4.2.1 of the paper (scale defaults to 1/sqrt(D)).
+    ``tile=(T_M, T_N)`` pins the schedule; ``out`` / ``lse_out`` let the caller own the outputs.
+    """
+    import torch
+
+    if causal:
+        raise NotImplementedError("causal masking is not part of this build")
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise ValueError(f"{name} must be a device tensor")
+        if t.dim() != 4:
+            raise ValueError(f"{name} must be [B, H, S, D]")
+        if not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous")
+    if q.dtype not in (torch.float16, torch.bfloat16) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share dtype float16 or bfloat16")
+    if q.shape != k.shape or q.shape != v.shape or k.device != q.device or v.device != q.device:
+        raise ValueError("q, k, v must have identical shape and device")
+    B, H, S, D = q.shape
+    dtype = F16 if q.dtype == torch.float16 else BF16
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
+        raise ValueError("out must match q in shape, dtype, device and be contiguous")
+    lse = None
+    if return_lse:
+        lse = lse_out if lse_out is not None else torch.empty((B, H, S), dtype=torch.float32, device=q.device)
+        if lse.shape != (B, H, S) or lse.dtype != torch.float32 or not lse.is_contiguous():
+            raise ValueError("lse_out must be contiguous float32 [B, H, S]")
+    tm, tn = tile if tile is not None else (0, 0)
+    with torch.cuda.device(q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        st = tiled_sdpa_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                               lse.data_ptr() if lse is not None else None,
+                               B, H, S, D, math.nan if scale is None else scale, dtype, stream,
+                               tm, tn, flags)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return (out, lse) if return_lse else out

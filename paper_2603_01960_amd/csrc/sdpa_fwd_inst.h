@@ -1,0 +1,56 @@
+// Instantiates the forward kernel for one (element type, head dim) over the tile grid
+// T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs) and provides its launcher.
+// The kernel table is fixed at build time: there is no JIT step to cache (Section 4.2.2).
+#pragma once
+#include <mutex>
+
+#include "sdpa_fwd_kernel.h"
+#include "sdpa_fwd_launch.h"
+
+namespace tsdpa {
+
+constexpr int kLdsPerCU = 160 * 1024;
+
+template <int D, int NW, int TN> constexpr int waves_per_simd() {
+    int wgs = kLdsPerCU / TileGeom<D, TN>::LDS_BYTES;
+    int w = wgs * NW / 4;
+    return w < 1 ? 1 : (w > 2 ? 2 : w);
+}
+
+template <typename T, int D, int NW, int TN>
+int launch_one(const LaunchArgs &a)
+{
+    constexpr int WPS = waves_per_simd<D, NW, TN>();
+    auto kern = sdpa_fwd_kernel<T, D, NW, TN, WPS>;
+    constexpr int lds_bytes = TileGeom<D, TN>::LDS_BYTES;
+    static std::once_flag once;
+    static hipError_t attr_err = hipSuccess;
+    std::call_once(once, [&] {
+        attr_err = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    });
+    if (attr_err != hipSuccess) return (int)attr_err;
+    constexpr int TM = NW * 32;
+    const int nQ = (a.S + TM - 1) / TM;
+    const int N = a.BH * nQ;
+    hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
+                       (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
+                       a.S, nQ, N, a.c, a.qsign, a.linear_grid);
+    return (int)hipGetLastError();
+}
+
+template <typename T, int D>
+int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a)
+{
+    const int key = tile_m * 1000 + tile_n;
+    switch (key) {
+        case 64032: return launch_one<T, D, 2, 32>(a);
+        case 64064: return launch_one<T, D, 2, 64>(a);
+        case 64128: return launch_one<T, D, 2, 128>(a);
+        case 128032: return launch_one<T, D, 4, 32>(a);
+        case 128064: return launch_one<T, D, 4, 64>(a);
+        case 128128: return launch_one<T, D, 4, 128>(a);
+        default: return (int)hipErrorInvalidValue;
+    }
+}
+
+}  // namespace tsdpa

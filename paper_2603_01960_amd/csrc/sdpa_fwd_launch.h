@@ -1,0 +1,25 @@
+// Host-side launch plumbing shared by the per-(dtype, D) instantiation files and the C-ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tsdpa {
+
+struct LaunchArgs {
+    const void *q, *k, *v;
+    void *o;
+    float *lse;
+    int BH, S;
+    float c;          // |scale| * log2(e)
+    uint32_t qsign;   // 0x80008000 when scale < 0 (sign folded into Q), else 0
+    int linear_grid;
+    hipStream_t stream;
+};
+
+// Each returns a hipError_t cast to int (0 = success); tile_m in {64,128}, tile_n in {32,64,128}.
+int launch_f16_d64(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_f16_d128(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_bf16_d64(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_bf16_d128(int tile_m, int tile_n, const LaunchArgs &a);
+
+}  // namespace tsdpa

@@ -1,0 +1,115 @@
+"""CPU-side checks of the C-ABI: the library loads, exports what include/tiled_sdpa.h declares,
+and rejects bad arguments before anything reaches a GPU (no compute calls here)."""
+import ctypes
+import math
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2603_01960_amd import binding
+
+ROOT = Path(__file__).resolve().parent.parent
+HEADER = ROOT / "include" / "tiled_sdpa.h"
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not binding.library_path().exists():
+        from paper_2603_01960_amd import build
+        build.build(force=True)
+    return binding.load_library()
+
+
+def declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", HEADER.read_text(), flags=re.S)
+    return sorted(set(re.findall(r"\b(tiled_sdpa_\w+)\s*\(", text)))
+
+
+def test_header_and_binding_agree_on_the_entry_points():
+    assert declared_functions() == sorted(binding.EXPORTS)
+
+
+def test_library_exports_every_declared_symbol(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert binding.version() >= 100
+    seen = set()
+    for code in range(0, 9):
+        s = binding.status_string(code)
+        assert s and s != "unknown status"
+        seen.add(s)
+    assert len(seen) == 9
+    assert binding.status_string(12345) == "unknown status"
+
+
+OK, NULL, SHAPE, DTYPE, BAD_D, ALIGN, TILE, SCALE = 0, 1, 2, 3, 4, 5, 6, 7
+P = 0x1000  # fake, aligned, never dereferenced: every case below fails validation before launch
+
+
+@pytest.mark.parametrize("kwargs,expect", [
+    (dict(dtype=2), DTYPE),
+    (dict(dtype=-1), DTYPE),
+    (dict(D=96), BAD_D),
+    (dict(D=0), BAD_D),
+    (dict(B=-1), SHAPE),
+    (dict(S=-5), SHAPE),
+    (dict(B=1 << 20, H=1 << 10, S=1 << 20), SHAPE),
+    (dict(B=0), OK),
+    (dict(S=0), OK),
+    (dict(S=0, q=None, o=None), OK),
+    (dict(q=None), NULL),
+    (dict(k=None), NULL),
+    (dict(v=None), NULL),
+    (dict(o=None), NULL),
+    (dict(q=P + 8), ALIGN),
+    (dict(o=P + 2), ALIGN),
+    (dict(lse=P + 2), ALIGN),
+    (dict(tile_m=32, tile_n=64), TILE),
+    (dict(tile_m=128, tile_n=0), TILE),
+    (dict(tile_m=128, tile_n=256), TILE),
+    (dict(scale=math.inf), SCALE),
+    (dict(scale=-math.inf), SCALE),
+])
+def test_validation_order_and_codes(lib, kwargs, expect):
+    a = dict(q=P, k=P, v=P, o=P, lse=None, B=1, H=2, S=128, D=64, scale=0.125, dtype=0,
+             stream=None, tile_m=0, tile_n=0, flags=0)
+    a.update(kwargs)
+    st = binding.tiled_sdpa_fwd_ex(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["S"],
+                                   a["D"], a["scale"], a["dtype"], a["stream"], a["tile_m"],
+                                   a["tile_n"], a["flags"])
+    assert st == expect, binding.status_string(st)
+
+
+def test_plain_entry_point_validates_too(lib):
+    assert binding.tiled_sdpa_fwd(None, P, P, P, None, 1, 1, 16, 64, 0.125, 0, None) == NULL
+    assert binding.tiled_sdpa_fwd(P, P, P, P, None, 1, 1, 16, 80, 0.125, 0, None) == BAD_D
+    assert binding.tiled_sdpa_fwd(None, None, None, None, None, 0, 4, 16, 64, 0.125, 1, None) == OK
+
+
+def test_default_tile_is_a_legal_tile(lib):
+    for S in (1, 32, 64, 197, 1024, 16384):
+        for D in (64, 128):
+            tm, tn = binding.default_tile(2, 4, S, D, binding.BF16)
+            assert tm in (64, 128) and tn in (32, 64, 128)
+    with pytest.raises(binding.TiledSdpaError):
+        binding.default_tile(1, 1, 16, 72, 0)
+
+
+def test_python_front_end_rejects_host_tensors_and_causal():
+    import torch
+    x = torch.zeros(1, 1, 4, 64, dtype=torch.float16)
+    with pytest.raises(ValueError):
+        binding.sdpa(x, x, x)
+    with pytest.raises(NotImplementedError):
+        binding.sdpa(x, x, x, causal=True)
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = ROOT / "paper_2603_01960_amd"
+    for path in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
+        text = path.read_text()
+        assert "oracle" not in text.lower(), path
