@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the tiled SDPA forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--tile TM,TN]
+
+A step is one forward pass (one kernel launch: the whole hot path) over one seeded synthetic
+batch that is already resident in HBM.  Policy follows the paper's harness (Section 4.2.3):
+W warm-up calls, synchronise, events around every timed call, median and p95 over the K calls.
+Prints ONE JSON line.  TFLOP/s = 4*B*H*S^2*D / t (the two matrix products, true S).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import platform
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense FP16/BF16 MFMA, published
+PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
+# scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
+MEASURED_TRAFFIC_BYTES = {}
+
+# The paper's own figures, other hardware (NVIDIA DGX GB10): context only, never a target.
+PAPER_CONTEXT = {
+    "hardware": "NVIDIA DGX GB10",
+    "fp16_noncausal_D128_S4096_tflops": 73.62,
+    "fp16_noncausal_D128_S8192_tflops": 73.38,
+}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: B2 H32 S8192 D128 BF16)")
+    ap.add_argument("--dtype", default=None, help="f16 / bf16 (default: the workload's first dtype)")
+    ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
+    ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
+    ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    return ap.parse_args()
+
+
+def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0):
+    from paper_2603_01960_amd.workloads import make_workload
+    w, q, k, v = make_workload(name, dtype)
+    dtype = dtype or w.dtypes[0]
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    o = torch.empty_like(qd)
+    run = lambda: pkg.sdpa(qd, kd, vd, out=o, tile=tile, flags=flags)
+    for _ in range(warmup):
+        run()
+    torch.cuda.synchronize()
+    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    t0 = time.perf_counter()
+    for i in range(steps):
+        starts[i].record()          # same (current) stream the kernel is enqueued on
+        run()
+        stops[i].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per_launch_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    assert torch.isfinite(o.float()).all().item(), "non-finite output"
+    return {
+        "workload": w, "dtype": dtype, "wall_s": wall,
+        "ms_per_step": 1e3 * wall / steps,
+        "kernel_ms_avg": sum(per_launch_ms) / steps,
+        "kernel_ms_median": statistics.median(per_launch_ms),
+        "kernel_ms_p95": per_launch_ms[min(steps - 1, int(0.95 * steps))],
+        "tensors": (q, k, v),
+    }
+
+
+def cpu_baseline(w, q, k, v, target_seconds):
+    """Time the unmodified float64 CPU checker on a bounded sample of the same workload."""
+    from oracle import sdpa_oracle
+    qn, kn, vn = (x.float().numpy() for x in (q, k, v))
+    # calibrate on a few rows, then size the sample for ~target_seconds
+    probe = list(range(0, w.S, max(1, w.S // 8)))[:8]
+    t = time.perf_counter()
+    sdpa_oracle.sdpa(qn, kn, vn, rows=probe)
+    dt = max(time.perf_counter() - t, 1e-4)
+    nrows = int(min(w.S, max(len(probe), len(probe) * target_seconds / dt)))
+    stride = max(1, w.S // nrows)
+    rows = list(range(0, w.S, stride))[:nrows]
+    t = time.perf_counter()
+    sdpa_oracle.sdpa(qn, kn, vn, rows=rows)
+    dt = time.perf_counter() - t
+    flops = 4.0 * w.BH * len(rows) * w.S * w.D
+    return {
+        "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": sdpa_oracle.num_threads(),
+        "kind": "oracle", "seconds": round(dt, 3),
+        "sample": f"{w.name}: all {w.BH} heads x {len(rows)} of {w.S} query rows (stride {stride}) "
+                  f"against all {w.S} keys, float64",
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (heads are independent, so more GPUs would each run "
+              "this same kernel on a slice of B*H); --gpus > 1 is not supported.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2603_01960_amd as pkg
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    pkg.load_library()      # no fallback: raises if the HIP library is not built
+    torch.cuda.set_device(0)
+    tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else None
+    flags = pkg.binding.FLAG_LINEAR_GRID if args.linear_grid else 0
+
+    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags)
+    w, dtype = r["workload"], r["dtype"]
+    tflops = w.flops / (r["ms_per_step"] * 1e-3) / 1e12
+    kern_tflops = w.flops / (r["kernel_ms_avg"] * 1e-3) / 1e12
+    tm, tn = tile if tile else pkg.binding.default_tile(w.B, w.H, w.S, w.D, pkg.F16 if dtype == "f16" else pkg.BF16)
+
+    # which roof bounds the kernel: arithmetic intensity on compulsory bytes vs the ridge point
+    comp_bytes = w.compulsory_bytes(2)
+    ridge = PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if w.flops / comp_bytes >= ridge:
+        roofline = {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_MFMA_TFLOPS,
+                    "unit": "TFLOP/s", "frac": round(kern_tflops / PEAK_MFMA_TFLOPS, 4)}
+    else:
+        gbs = comp_bytes / (r["kernel_ms_avg"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dtype))
+    roofline["kernel"] = f"sdpa_fwd_kernel<{dtype},D={w.D},T_M={tm},T_N={tn}>"
+    roofline["kernel_ms_avg"] = round(r["kernel_ms_avg"], 5)
+    roofline["kernel_ms_median"] = round(r["kernel_ms_median"], 5)
+    roofline["kernel_ms_p95"] = round(r["kernel_ms_p95"], 5)
+    roofline["algorithmic_flops_per_launch"] = w.flops
+    roofline["compulsory_hbm_bytes_per_launch"] = comp_bytes
+
+    out = {
+        "metric": "SDPA forward TFLOP/s (4*B*H*S^2*D / t)", "value": round(tflops, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: SDPA fwd non-causal B={w.B} H={w.H} S={w.S} D={w.D} {dtype}",
+                   "tile_m": tm, "tile_n": tn, "seed": w.seed, "qk_std": round(w.qk_std, 6),
+                   "tokens_per_s": round(w.BH * w.S / (r["ms_per_step"] * 1e-3), 1)},
+        "roofline": roofline,
+        "frac_of_mfma_peak": round(tflops / PEAK_MFMA_TFLOPS, 4),
+        "paper_context": PAPER_CONTEXT,
+        "env": {"torch": torch.__version__, "hip": torch.version.hip, "device": torch.cuda.get_device_name(0),
+                "library_version": pkg.version(), "host": platform.processor() or platform.machine()},
+    }
+
+    if args.all_workloads:
+        others = {}
+        for name, dts in (("C1", ["f16"]), ("C2", ["f16", "bf16"]), ("C3", ["bf16"]), ("C4", ["bf16"]), ("C5", ["f16"])):
+            for dt in dts:
+                rr = time_workload(pkg, torch, name, dt, max(10, args.steps // 2), args.warmup)
+                ww = rr["workload"]
+                others[f"{name}_{dt}"] = {
+                    "kernel_ms_median": round(rr["kernel_ms_median"], 5),
+                    "tflops": round(ww.flops / (rr["kernel_ms_median"] * 1e-3) / 1e12, 2),
+                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (rr["kernel_ms_median"] * 1e-3) / 1e9, 1)}
+                del rr
+        out["all_workloads"] = others
+
+    if not args.no_cpu_baseline:
+        q, k, v = r["tensors"]
+        out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_seconds)
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

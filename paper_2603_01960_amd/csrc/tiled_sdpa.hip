@@ -18,9 +18,10 @@ bool valid_tile(int tm, int tn) { return (tm == 64 || tm == 128) && (tn == 32 ||
 void pick_tile(int BH, int S, int D, int *tm, int *tn)
 {
     (void)BH;
-    (void)D;
+    // From the tile sweep on MI355X: 128 query rows per workgroup everywhere; at D = 128 the
+    // 32-row K/V tile keeps the kernel at two wavefronts per SIMD without register spills.
     *tm = 128;
-    *tn = 64;
+    *tn = (D == 128) ? 32 : 64;
     if (S <= 64) *tm = 64;
     if (S <= 32) *tn = 32;
 }
