@@ -43,7 +43,11 @@ enum {
 
 /* flags for tiled_sdpa_fwd_ex */
 enum {
-    TSDPA_FLAG_LINEAR_GRID = 1u  /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
+    TSDPA_FLAG_LINEAR_GRID = 1u, /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
+    TSDPA_FLAG_EXACT_MAX = 2u    /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
+                                    Default: raise it only when the tile maximum exceeds it by more than
+                                    2^8, which gives the same O and lse up to rounding and skips most
+                                    rescales of the accumulator. */
 };
 
 /*

@@ -6,6 +6,8 @@
 //   * a workgroup has NW wavefronts; each wavefront owns 32 query rows (T_M = 32*NW) and keeps
 //     its Q rows in registers as MFMA B-operands for the whole loop;
 //   * K and V tiles are staged global -> registers -> LDS, double buffered, one barrier per tile;
+//     K runs one tile ahead of V so the scores of tile j+1 (matrix pipe) overlap the softmax of
+//     tile j (vector ALU) inside every wavefront;
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: in the 32x32
 //     accumulator layout a lane then owns ONE query column and 16 of the 32 key rows, so the row
 //     maximum / sum of Eqs. 2-3 are in-lane reductions plus one exchange with lane^32, and m, l and
@@ -83,8 +85,7 @@ template <int D, int TN> struct TileGeom {
     static constexpr int VS = D * 2 + 64;  // V row stride: 4 consecutive rows x 64 B tile the 64 banks (tr reads)
     static constexpr int KBYTES = TN * KS;
     static constexpr int VBYTES = TN * VS;
-    static constexpr int STAGE = KBYTES + VBYTES;
-    static constexpr int LDS_BYTES = 2 * STAGE;
+    static constexpr int LDS_BYTES = 2 * (KBYTES + VBYTES);   // two K slots, then two V slots
 };
 
 // Workgroup -> (head, query tile).  Hardware deals consecutive workgroup ids round-robin over the
@@ -101,7 +102,7 @@ template <typename T, int D, int NW, int TN, int WPS>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
-                uint32_t qsign, int linear_grid)
+                float tau, uint32_t qsign, int linear_grid)
 {
     using E = Elem<T>;
     using vec8 = typename E::vec8;
@@ -136,48 +137,48 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     const int nT = (S + TN - 1) / TN;
-    u32x4 kst[NLD], vst[NLD];
 
-    auto load_tile = [&](int j) {
+    // ---- staging of one [TN x D] tile: HBM -> registers (128-bit, coalesced) -> LDS rows
+    struct Stage { u32x4 r[NLD]; };
+    auto load_tile = [&](const T *base, int j, Stage &st) {
 #pragma unroll
         for (int it = 0; it < NLD; ++it) {
             const int ci = tid + it * NT;
             const int row = ci / CPR, cc = ci % CPR;
             int key = j * TN + row;
-            key = key < S ? key : S - 1;   // rows past S re-read the last row: finite data, masked below
-            const size_t off = (size_t)key * D + cc * 8;
-            kst[it] = *(const u32x4 *)(kh + off);
-            vst[it] = *(const u32x4 *)(vh + off);
+            key = key < S ? key : S - 1;   // rows past S re-read the last row: finite data, masked later
+            st.r[it] = *(const u32x4 *)(base + (size_t)key * D + cc * 8);
         }
     };
-    auto store_tile = [&](int buf) {
-        const lds_ptr kb = lds + buf * G::STAGE, vb = kb + G::KBYTES;
+    auto store_tile = [&](lds_ptr dst, int stride, const Stage &st) {
 #pragma unroll
         for (int it = 0; it < NLD; ++it) {
             const int ci = tid + it * NT;
             const int row = ci / CPR, cc = ci % CPR;
-            lds_write128(kb + row * G::KS + cc * 16, kst[it]);
-            lds_write128(vb + row * G::VS + cc * 16, vst[it]);
+            lds_write128(dst + row * stride + cc * 16, st.r[it]);
         }
     };
+    auto kslot = [&](int j) { return lds + (j & 1) * G::KBYTES; };
+    auto vslot = [&](int j) { return lds + 2 * G::KBYTES + (j & 1) * G::VBYTES; };
 
     f32x16 oacc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
-    float m_run = -INFINITY;   // running maximum of s*c (log2 domain), Eq. 2
-    float l_run = 0.f;         // this lane's share of the normaliser, Eq. 3 (lane^32 holds the rest)
+    // Online-softmax state (Eqs. 2-4), all in the log2 domain of s*c.  m_ref is the reference the
+    // exponentials are taken against: it is raised to the tile maximum only when that exceeds it by
+    // more than tau (tau = 0 is Eq. 2 literally).  With a stale reference the weights are merely
+    // scaled by a common factor <= 2^tau per row, which cancels in o/l and in m_ref + log2(l).
+    float m_ref = -INFINITY;
+    float l_run = 0.f;         // this lane's share of the normaliser (lane^32 holds the rest)
 
     // per-lane constant parts of the LDS read addresses
     const int k_lane_off = l32 * G::KS + g * 16;
     const int v_lane_off = (g * 4 + ((lane & 15) >> 2)) * G::VS + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
 
-    auto compute_tile = [&](int buf, int j, auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
-        const lds_ptr kb = lds + buf * G::STAGE, vb = kb + G::KBYTES;
-        // ---- scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
-        f32x16 sacc[NB];
+    // scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
+    auto scores = [&](lds_ptr kb, f32x16 (&sacc)[NB]) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
@@ -188,6 +189,11 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
             }
         }
+    };
+
+    // Eqs. 2-3 on one tile of scores; leaves the 16-bit weights (MFMA B-operands) in pb
+    auto softmax = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         const int key0 = j * TN + g * 4;
         if constexpr (TAIL) {
 #pragma unroll
@@ -196,36 +202,42 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 for (int i = 0; i < 16; ++i)
                     if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) >= S) sacc[nb][i] = -INFINITY;
         }
-        // ---- Eq. 2: running maximum
         float mx = sacc[0][0];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][i]);
         mx = pair_max(mx);
-        const float m_new = fmaxf(m_run, mx * c);
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
-        m_run = m_new;
-        // ---- p = 2^(s*c - m); Eq. 3 uses the unrounded FP32 p, the PV product the 16-bit rounded p
+        const float m_tile = mx * c;
+        const bool grow = m_tile > m_ref + tau;     // always true on the first tile (m_ref = -inf)
+        if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // wavefront-uniform: rescale only when some row needs it
+            const float m_new = grow ? m_tile : m_ref;
+            const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exactly 1 for rows that keep m_ref
+            m_ref = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        }
+        // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p
         float psum = 0.f;
-        vec8 pb[NB][2];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[nb][i], c, -m_new));
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[nb][i], c, -m_ref));
                 if constexpr (TAIL) {
                     if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) >= S) p = 0.f;
                 }
                 psum += p;
                 pb[nb][i >> 3][i & 7] = (T)p;
             }
-        l_run = l_run * alpha + psum;
-        // ---- Eq. 4: rescale, then O^T += V^T P^T
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
+        l_run += psum;
+    };
+
+    // Eq. 4: O^T += V^T P^T
+    auto accumulate = [&](lds_ptr vb, const vec8 (&pb)[NB][2]) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -241,20 +253,42 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 }
     };
 
-    // ---- pipeline: tile j+1 travels HBM -> registers while tile j is consumed from LDS
-    load_tile(0);
-    store_tile(0);
+    // ---- software pipeline.  K runs one tile ahead of V: while the VALU does the softmax of tile j,
+    // the matrix pipe already computes the scores of tile j+1.  In iteration j the LDS holds K(j+1)
+    // and V(j); K(j+2) and V(j+1) travel HBM -> registers and are written to the slots that K(j) and
+    // V(j-1) occupied, whose last readers finished before the barrier that ended iteration j-1.
+    Stage sk, sv;
+    load_tile(kh, 0, sk);
+    load_tile(vh, 0, sv);
+    store_tile(kslot(0), G::KS, sk);
+    store_tile(vslot(0), G::VS, sv);
+    if (nT > 1) {
+        load_tile(kh, 1, sk);
+        store_tile(kslot(1), G::KS, sk);
+    }
     __syncthreads();
-    for (int j = 0; j < nT; ++j) {
-        const bool more = j + 1 < nT;
-        if (more) load_tile(j + 1);
-        if ((j + 1) * TN > S)
-            compute_tile(j & 1, j, std::true_type{});
-        else
-            compute_tile(j & 1, j, std::false_type{});
-        if (more) store_tile((j + 1) & 1);
+    f32x16 s_cur[NB], s_nxt[NB];
+    vec8 pb[NB][2];
+    scores(kslot(0), s_cur);
+    __syncthreads();   // iteration 0 overwrites K slot 0: every wavefront must have read it first
+    for (int j = 0; j + 1 < nT; ++j) {
+        const int jk = j + 2 < nT ? j + 2 : nT - 1;   // past the end: reload the last tile (never read)
+        load_tile(kh, jk, sk);
+        load_tile(vh, j + 1, sv);
+        scores(kslot(j + 1), s_nxt);
+        softmax(s_cur, j, pb, std::false_type{});
+        accumulate(vslot(j), pb);
+        store_tile(kslot(j + 2), G::KS, sk);
+        store_tile(vslot(j + 1), G::VS, sv);
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
         __syncthreads();
     }
+    if (nT * TN != S)
+        softmax(s_cur, nT - 1, pb, std::true_type{});
+    else
+        softmax(s_cur, nT - 1, pb, std::false_type{});
+    accumulate(vslot(nT - 1), pb);
 
     // ---- O_i = o_i / l_i (Section 4.1.2), rounded once to the 16-bit output type
     const float l_tot = pair_sum(l_run);
@@ -271,7 +305,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 *(vec4 *)(orow + db * 32 + q4 * 8 + g * 4) = out;
             }
         if (lse != nullptr && g == 0)
-            lse[(size_t)head * S + qrow] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+            lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     }
 }
 

@@ -11,6 +11,7 @@ struct LaunchArgs {
     float *lse;
     int BH, S;
     float c;          // |scale| * log2(e)
+    float tau;        // lazy-rescale threshold in log2 units (0 = raise the reference on every new maximum)
     uint32_t qsign;   // 0x80008000 when scale < 0 (sign folded into Q), else 0
     int linear_grid;
     hipStream_t stream;

@@ -95,6 +95,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     a.BH = B * H;
     a.S = S;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
+    a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
     a.linear_grid = (flags & TSDPA_FLAG_LINEAR_GRID) ? 1 : 0;
     a.stream = (hipStream_t)stream;
