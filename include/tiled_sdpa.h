@@ -32,7 +32,7 @@ enum { TSDPA_F16 = 0, TSDPA_BF16 = 1 };
 enum {
     TSDPA_OK = 0,
     TSDPA_ERR_NULL_PTR = 1,      /* q, k, v or o is NULL while B*H*S > 0                    */
-    TSDPA_ERR_BAD_SHAPE = 2,     /* negative B, H or S, or B*H*ceil(S/tile_m) overflows int */
+    TSDPA_ERR_BAD_SHAPE = 2,     /* negative B, H or S; B*H*ceil(S/64) or (S+256)*D*2 overflows int */
     TSDPA_ERR_BAD_DTYPE = 3,     /* dtype is neither TSDPA_F16 nor TSDPA_BF16               */
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64 or 128                                      */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */

@@ -5,8 +5,12 @@
 // tiles of T_N rows):
 //   * a workgroup has NW wavefronts; each wavefront owns 32 query rows (T_M = 32*NW) and keeps
 //     its Q rows in registers as MFMA B-operands for the whole loop;
-//   * K and V tiles are staged global -> registers -> LDS, double buffered, one barrier per tile;
-//     K runs one tile ahead of V so the scores of tile j+1 (matrix pipe) overlap the softmax of
+//   * K and V tiles go HBM -> LDS directly (buffer_load_dwordx4 ... lds: no staging registers, no
+//     LDS write instructions), double buffered, one barrier per tile.  Such a load writes 64 lanes x
+//     16 B contiguously, so rows cannot be padded; bank conflicts are avoided by an XOR swizzle of
+//     the 16-byte chunks within each row, applied through the choice of the global address each
+//     lane fetches.  Rows past S are never fetched: the buffer descriptor's range check returns 0;
+//   * K runs one tile ahead of V so the scores of tile j+1 (matrix pipe) overlap the softmax of
 //     tile j (vector ALU) inside every wavefront;
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: in the 32x32
 //     accumulator layout a lane then owns ONE query column and 16 of the 32 key rows, so the row
@@ -79,13 +83,18 @@ __device__ __forceinline__ float pair_sum(float x) {
     return __builtin_bit_cast(float, r0) + __builtin_bit_cast(float, r1);
 }
 
-// LDS geometry shared by host (dynamic LDS size) and device.
+// LDS geometry shared by host (dynamic LDS size) and device.  A tile is TN rows of D 16-bit values,
+// unpadded; within a row the 16-byte chunks are XOR-swizzled:
+//   K: chunk c of row r sits at c ^ kswz(r).  The score MFMA's A-operand read has 16 lanes fetch the
+//      same chunk of 16 consecutive rows; the swizzle spreads them over all 64 banks.
+//   V: 64-byte block b of row r sits at b ^ vswz(r).  The transposing read has 32 lanes fetch one
+//      64-byte block of 4 consecutive rows; the swizzle puts those on 4 x 16 distinct banks.
 template <int D, int TN> struct TileGeom {
-    static constexpr int KS = D * 2 + 16;  // K row stride (bytes): +4 banks per row -> 128-bit row reads spread
-    static constexpr int VS = D * 2 + 64;  // V row stride: 4 consecutive rows x 64 B tile the 64 banks (tr reads)
-    static constexpr int KBYTES = TN * KS;
-    static constexpr int VBYTES = TN * VS;
-    static constexpr int LDS_BYTES = 2 * (KBYTES + VBYTES);   // two K slots, then two V slots
+    static constexpr int ROW = D * 2;            // bytes per row
+    static constexpr int TILE = TN * ROW;        // bytes per K or V tile
+    static constexpr int LDS_BYTES = 4 * TILE;   // K slots 0,1 then V slots 0,1
+    static __host__ __device__ constexpr int kswz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+    static __host__ __device__ constexpr int vswz(int r) { return D == 128 ? (r & 3) : ((r >> 1) & 1); }
 };
 
 // Workgroup -> (head, query tile).  Hardware deals consecutive workgroup ids round-robin over the
@@ -98,32 +107,37 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
     return x * base + (x < rem ? x : rem) + y;
 }
 
+// s_waitcnt vmcnt(0) with the other counters left at their maxima (gfx9 encoding)
+#define TSDPA_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)
+
 template <typename T, int D, int NW, int TN, int WPS>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
                 float tau, uint32_t qsign, int linear_grid)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     using E = Elem<T>;
     using vec8 = typename E::vec8;
     using vec4 = typename E::vec4;
     using G = TileGeom<D, TN>;
-    constexpr int NT = NW * 64, TM = NW * 32;
-    constexpr int CPR = D / 8;            // 16-byte chunks per row
-    constexpr int NLD = TN * CPR / NT;    // chunks per thread per tensor per tile
-    static_assert(NLD >= 1 && (TN * CPR) % NT == 0, "tile does not divide over the workgroup");
+    constexpr int TM = NW * 32;
+    constexpr int CPR = D / 8;                    // 16-byte chunks per row
+    constexpr int NLD = TN * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
+    static_assert(NLD >= 1 && (TN * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
     constexpr int NB = TN / 32, KK = D / 16, DB = D / 32;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const lds_ptr lds = (lds_ptr)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
 
     const int wg = remap_workgroup(blockIdx.x, N, linear_grid != 0);
     const int head = wg / nQ, qt = wg - head * nQ;
     const size_t head_off = (size_t)head * (size_t)S * D;
-    const T *qh = q + head_off, *kh = k + head_off, *vh = v + head_off;
+    const T *qh = q + head_off;
 
     // ---- Q rows of this wavefront as MFMA B-operands: lane holds Q[row l32][kk*16 + g*8 .. +7]
     const int qrow = qt * TM + wave * 32 + l32;
@@ -138,28 +152,28 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 
     const int nT = (S + TN - 1) / TN;
 
-    // ---- staging of one [TN x D] tile: HBM -> registers (128-bit, coalesced) -> LDS rows
-    struct Stage { u32x4 r[NLD]; };
-    auto load_tile = [&](const T *base, int j, Stage &st) {
+    // ---- K/V tiles: HBM -> LDS.  One buffer descriptor per tensor covers exactly this head's S rows,
+    // so a row index >= S reads as zeros instead of touching memory.  Load instruction `it` of this
+    // wavefront fills LDS chunks [(it*NW + wave)*64, +64) of the tile; lane `lane` fills chunk p of
+    // that range and therefore fetches the global chunk that the swizzle maps to position p.
+    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + head_off), (short)0, S * G::ROW, 0x00020000);
+    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + head_off), (short)0, S * G::ROW, 0x00020000);
+    int k_goff[NLD], v_goff[NLD];
 #pragma unroll
-        for (int it = 0; it < NLD; ++it) {
-            const int ci = tid + it * NT;
-            const int row = ci / CPR, cc = ci % CPR;
-            int key = j * TN + row;
-            key = key < S ? key : S - 1;   // rows past S re-read the last row: finite data, masked later
-            st.r[it] = *(const u32x4 *)(base + (size_t)key * D + cc * 8);
-        }
-    };
-    auto store_tile = [&](lds_ptr dst, int stride, const Stage &st) {
+    for (int it = 0; it < NLD; ++it) {
+        const int p = (it * NW + wave) * 64 + lane;
+        const int r = p / CPR, cp = p % CPR;
+        k_goff[it] = r * G::ROW + ((cp ^ G::kswz(r)) << 4);
+        v_goff[it] = r * G::ROW + ((cp ^ (G::vswz(r) << 2)) << 4);
+    }
+    auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) {
+        const int soff = j * G::TILE;     // wavefront-uniform; rows >= S fall outside the descriptor
 #pragma unroll
-        for (int it = 0; it < NLD; ++it) {
-            const int ci = tid + it * NT;
-            const int row = ci / CPR, cc = ci % CPR;
-            lds_write128(dst + row * stride + cc * 16, st.r[it]);
-        }
+        for (int it = 0; it < NLD; ++it)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
+                                                     goff[it], soff, 0, 0);
     };
-    auto kslot = [&](int j) { return lds + (j & 1) * G::KBYTES; };
-    auto vslot = [&](int j) { return lds + 2 * G::KBYTES + (j & 1) * G::VBYTES; };
+    constexpr int KSLOT0 = 0, KSLOT1 = G::TILE, VSLOT0 = 2 * G::TILE, VSLOT1 = 3 * G::TILE;
 
     f32x16 oacc[DB];
 #pragma unroll
@@ -173,22 +187,32 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     float m_ref = -INFINITY;
     float l_run = 0.f;         // this lane's share of the normaliser (lane^32 holds the rest)
 
-    // per-lane constant parts of the LDS read addresses
-    const int k_lane_off = l32 * G::KS + g * 16;
-    const int v_lane_off = (g * 4 + ((lane & 15) >> 2)) * G::VS + (((lane >> 4) & 1) * 16 + (lane & 3) * 4) * 2;
+    // ---- per-lane LDS read addresses (loop invariant; tile slot, nb, ks enter as immediates)
+    // K: row l32 (+32*nb), chunk (2*kk + g) ^ kswz(row)
+    int k_roff[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) k_roff[kk] = l32 * G::ROW + (((2 * kk + g) ^ G::kswz(l32)) << 4);
+    // V (transposing read): row g*4 + (lane%16)/4 (+ multiples of 8), 64-byte block db ^ vswz(row),
+    // then 32 B for the upper 16 lanes of each 32 and 8 B per lane%4
+    const int v_row = g * 4 + ((lane & 15) >> 2);
+    int v_roff[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+        v_roff[db] = v_row * G::ROW + ((db ^ G::vswz(v_row)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
     // scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
-    auto scores = [&](lds_ptr kb, f32x16 (&sacc)[NB]) {
+    auto scores = [&](int kslot, f32x16 (&sacc)[NB]) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) sacc[nb][i] = 0.f;
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) {
-                u32x4 raw = lds_read128(kb + k_lane_off + nb * 32 * G::KS + kk * 32);
+        for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {   // nb innermost: independent accumulators alternate
+                u32x4 raw = lds_read128(lds + kslot + nb * 32 * G::ROW + k_roff[kk]);
                 sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
             }
-        }
     };
 
     // Eqs. 2-3 on one tile of scores; leaves the 16-bit weights (MFMA B-operands) in pb
@@ -221,7 +245,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
         }
         // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p
-        float psum = 0.f;
+        float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -230,14 +254,14 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 if constexpr (TAIL) {
                     if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) >= S) p = 0.f;
                 }
-                psum += p;
+                psum[i & 3] += p;
                 pb[nb][i >> 3][i & 7] = (T)p;
             }
-        l_run += psum;
+        l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
     };
 
     // Eq. 4: O^T += V^T P^T
-    auto accumulate = [&](lds_ptr vb, const vec8 (&pb)[NB][2]) {
+    auto accumulate = [&](int vslot, const vec8 (&pb)[NB][2]) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -245,50 +269,58 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
                     // k-slots 0..3 / 4..7 of this lane <-> key rows base+g*4+0..3 / base+8+g*4+0..3
-                    const lds_ptr p0 = vb + v_lane_off + (nb * 32 + ks * 16) * G::VS + db * 64;
+                    const lds_ptr p0 = lds + vslot + (nb * 32 + ks * 16) * G::ROW + v_roff[db];
                     i16x4 lo = lds_read_tr16(p0);
-                    i16x4 hi = lds_read_tr16(p0 + 8 * G::VS);
+                    i16x4 hi = lds_read_tr16(p0 + 8 * G::ROW);
                     i16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     oacc[db] = E::mfma(__builtin_bit_cast(vec8, a), pb[nb][ks], oacc[db]);
                 }
     };
 
-    // ---- software pipeline.  K runs one tile ahead of V: while the VALU does the softmax of tile j,
-    // the matrix pipe already computes the scores of tile j+1.  In iteration j the LDS holds K(j+1)
-    // and V(j); K(j+2) and V(j+1) travel HBM -> registers and are written to the slots that K(j) and
-    // V(j-1) occupied, whose last readers finished before the barrier that ended iteration j-1.
-    Stage sk, sv;
-    load_tile(kh, 0, sk);
-    load_tile(vh, 0, sv);
-    store_tile(kslot(0), G::KS, sk);
-    store_tile(vslot(0), G::VS, sv);
-    if (nT > 1) {
-        load_tile(kh, 1, sk);
-        store_tile(kslot(1), G::KS, sk);
-    }
-    __syncthreads();
-    f32x16 s_cur[NB], s_nxt[NB];
+    // ---- software pipeline, unrolled by two so that LDS slots and score registers alternate by name.
+    // K runs one tile ahead of V: while the VALU does the softmax of tile j, the matrix pipe already
+    // computes the scores of tile j+1.  In step j the LDS holds K(j+1) and V(j); K(j+2) and V(j+1) are
+    // in flight into the slots that K(j) and V(j-1) occupied, whose last readers finished before the
+    // barrier that ended step j-1.
+    f32x16 s_a[NB], s_b[NB];
     vec8 pb[NB][2];
-    scores(kslot(0), s_cur);
-    __syncthreads();   // iteration 0 overwrites K slot 0: every wavefront must have read it first
-    for (int j = 0; j + 1 < nT; ++j) {
-        const int jk = j + 2 < nT ? j + 2 : nT - 1;   // past the end: reload the last tile (never read)
-        load_tile(kh, jk, sk);
-        load_tile(vh, j + 1, sv);
-        scores(kslot(j + 1), s_nxt);
-        softmax(s_cur, j, pb, std::false_type{});
-        accumulate(vslot(j), pb);
-        store_tile(kslot(j + 2), G::KS, sk);
-        store_tile(vslot(j + 1), G::VS, sv);
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) s_cur[nb] = s_nxt[nb];
+    load_tile(k_rsrc, k_goff, 0, lds + KSLOT0);
+    load_tile(v_rsrc, v_goff, 0, lds + VSLOT0);
+    load_tile(k_rsrc, k_goff, 1, lds + KSLOT1);   // past the end when nT == 1: zeros, never used
+    TSDPA_WAIT_VMCNT0();
+    __syncthreads();
+    scores(KSLOT0, s_a);
+    __syncthreads();   // step 0 overwrites K slot 0: every wavefront must have read it first
+
+    // step with tile j's scores in `cur`: PAR = j & 1 selects the slots
+    auto step = [&](int j, f32x16 (&cur)[NB], f32x16 (&nxt)[NB], auto par_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        load_tile(k_rsrc, k_goff, j + 2, lds + (PAR ? KSLOT1 : KSLOT0));
+        load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
+        scores(PAR ? KSLOT0 : KSLOT1, nxt);
+        softmax(cur, j, pb, std::false_type{});
+        accumulate(PAR ? VSLOT1 : VSLOT0, pb);
+        TSDPA_WAIT_VMCNT0();
         __syncthreads();
+    };
+    auto last = [&](f32x16 (&cur)[NB], int vslot) {
+        if (nT * TN != S)
+            softmax(cur, nT - 1, pb, std::true_type{});
+        else
+            softmax(cur, nT - 1, pb, std::false_type{});
+        accumulate(vslot, pb);
+    };
+    int j = 0;
+    for (; j + 2 < nT; j += 2) {
+        step(j, s_a, s_b, std::integral_constant<int, 0>{});
+        step(j + 1, s_b, s_a, std::integral_constant<int, 1>{});
     }
-    if (nT * TN != S)
-        softmax(s_cur, nT - 1, pb, std::true_type{});
-    else
-        softmax(s_cur, nT - 1, pb, std::false_type{});
-    accumulate(vslot(nT - 1), pb);
+    if (j + 1 < nT) {          // two tiles left: j (even) then j+1 (odd, last)
+        step(j, s_a, s_b, std::integral_constant<int, 0>{});
+        last(s_b, VSLOT1);
+    } else {                   // one tile left: j (even, last)
+        last(s_a, VSLOT0);
+    }
 
     // ---- O_i = o_i / l_i (Section 4.1.2), rounded once to the 16-bit output type
     const float l_tot = pair_sum(l_run);
@@ -307,6 +339,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         if (lse != nullptr && g == 0)
             lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     }
+#endif
 }
 
 }  // namespace tsdpa

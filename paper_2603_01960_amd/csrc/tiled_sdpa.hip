@@ -18,10 +18,11 @@ bool valid_tile(int tm, int tn) { return (tm == 64 || tm == 128) && (tn == 32 ||
 void pick_tile(int BH, int S, int D, int *tm, int *tn)
 {
     (void)BH;
-    // From the tile sweep on MI355X: 128 query rows per workgroup everywhere; at D = 128 the
-    // 32-row K/V tile keeps the kernel at two wavefronts per SIMD without register spills.
+    // From the tile sweep on MI355X: 128 query rows per workgroup and 64-row K/V tiles (64 KB of LDS at
+    // D = 128, two workgroups per CU) win at every configuration measured.
     *tm = 128;
-    *tn = (D == 128) ? 32 : 64;
+    *tn = 64;
+    (void)D;
     if (S <= 64) *tm = 64;
     if (S <= 32) *tn = 32;
 }
@@ -35,6 +36,8 @@ int validate_shape(int B, int H, int S, int D, int dtype)
     // the grid is B*H*ceil(S/tile_m) <= B*H*ceil(S/64) workgroups and must fit an int
     if (bh > 0 && S > 0 && bh * (((int64_t)S + 63) / 64) > (int64_t)std::numeric_limits<int>::max())
         return TSDPA_ERR_BAD_SHAPE;
+    // one head's K (or V) is addressed through a 32-bit byte range, prefetch distance included
+    if (((int64_t)S + 256) * D * 2 > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
     return TSDPA_OK;
 }
 
