@@ -215,8 +215,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             }
     };
 
-    // Eqs. 2-3 on one tile of scores; leaves the 16-bit weights (MFMA B-operands) in pb
-    auto softmax = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto tail_tag) {
+    // Eq. 2 on one tile of scores: tile maximum, reference update and (rarely) the rescale of Eqs. 3-4.
+    // Kept apart from the exponentials because it ends in a branch: everything after it (scores of the
+    // next tile, exponentials, PV product) then forms one straight-line block the scheduler can interleave.
+    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto tail_tag) {
         constexpr bool TAIL = decltype(tail_tag)::value;
         const int key0 = j * TN + g * 4;
         if constexpr (TAIL) {
@@ -244,7 +246,12 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
                 for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
         }
-        // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p
+    };
+    // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p,
+    // left in pb as MFMA B-operands
+    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto tail_tag) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
+        const int key0 = j * TN + g * 4;
         float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -297,17 +304,21 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         constexpr int PAR = decltype(par_tag)::value;
         load_tile(k_rsrc, k_goff, j + 2, lds + (PAR ? KSLOT1 : KSLOT0));
         load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
+        row_max(cur, j, std::false_type{});
         scores(PAR ? KSLOT0 : KSLOT1, nxt);
-        softmax(cur, j, pb, std::false_type{});
+        exponentials(cur, j, pb, std::false_type{});
         accumulate(PAR ? VSLOT1 : VSLOT0, pb);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
     auto last = [&](f32x16 (&cur)[NB], int vslot) {
-        if (nT * TN != S)
-            softmax(cur, nT - 1, pb, std::true_type{});
-        else
-            softmax(cur, nT - 1, pb, std::false_type{});
+        if (nT * TN != S) {
+            row_max(cur, nT - 1, std::true_type{});
+            exponentials(cur, nT - 1, pb, std::true_type{});
+        } else {
+            row_max(cur, nT - 1, std::false_type{});
+            exponentials(cur, nT - 1, pb, std::false_type{});
+        }
         accumulate(vslot, pb);
     };
     int j = 0;
