@@ -45,7 +45,6 @@ def parse_args():
     ap.add_argument("--dtype", default=None, help="f16 / bf16 (default: the workload's first dtype)")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
-    ap.add_argument("--wide", action="store_true", help="tile_m=128/256 with 64-row wavefronts (TSDPA_FLAG_WIDE_WAVES)")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
@@ -125,7 +124,6 @@ def main():
     torch.cuda.set_device(0)
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else None
     flags = (pkg.binding.FLAG_LINEAR_GRID if args.linear_grid else 0) \
-        | (pkg.binding.FLAG_WIDE_WAVES if args.wide else 0) \
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0)
 
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags)

@@ -36,8 +36,7 @@ enum {
     TSDPA_ERR_BAD_DTYPE = 3,     /* dtype is neither TSDPA_F16 nor TSDPA_BF16               */
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64 or 128                                      */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
-    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128,256} x {32,64,128}, or
-                                    tile_m = 256 with tile_n = 32 at D = 64 without wide waves */
+    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}          */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8         /* the HIP runtime refused the launch                      */
 };
@@ -45,13 +44,10 @@ enum {
 /* flags for tiled_sdpa_fwd_ex */
 enum {
     TSDPA_FLAG_LINEAR_GRID = 1u, /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
-    TSDPA_FLAG_EXACT_MAX = 2u,   /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
+    TSDPA_FLAG_EXACT_MAX = 2u    /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
                                     Default: raise it only when the tile maximum exceeds it by more than
                                     2^8, which gives the same O and lse up to rounding and skips most
                                     rescales of the accumulator. */
-    TSDPA_FLAG_WIDE_WAVES = 4u   /* tile_m = 128 / 256 only: wavefronts of 64 query rows (2 resp. 4 per workgroup,
-                                    one per SIMD, every K/V fragment read from LDS feeds two MFMAs) instead
-                                    of 32-row wavefronts (4 resp. 8 per workgroup, two per SIMD). */
 };
 
 /*
@@ -77,10 +73,9 @@ int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *
 
 /*
  * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
- * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128,256}, tile_n in
+ * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
  * {32,64,128}; tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
- * tiled_sdpa_fwd uses.  The staging depth (LDS ring slots per tensor, 2 to 4) follows from the
- * tile: as many as fit the LDS share of a workgroup.  The result does not depend on the tile choice beyond rounding order.
+ * tiled_sdpa_fwd uses.  The result does not depend on the tile choice beyond rounding order.
  */
 int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
                       int B, int H, int S, int D, float scale, int dtype, void *stream,

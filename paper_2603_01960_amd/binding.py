@@ -13,7 +13,6 @@ from pathlib import Path
 F16, BF16 = 0, 1
 FLAG_LINEAR_GRID = 1
 FLAG_EXACT_MAX = 2
-FLAG_WIDE_WAVES = 4
 
 _PKG = Path(__file__).resolve().parent
 _LIB_PATH = _PKG / "libtiled_sdpa.so"

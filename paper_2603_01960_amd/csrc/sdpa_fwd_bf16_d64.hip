@@ -2,5 +2,5 @@
 #include "sdpa_fwd_inst.h"
 
 namespace tsdpa {
-int launch_bf16_d64(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<__bf16, 64>(tile_m, tile_n, a.wide != 0, a); }
+int launch_bf16_d64(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<__bf16, 64>(tile_m, tile_n, a); }
 }  // namespace tsdpa

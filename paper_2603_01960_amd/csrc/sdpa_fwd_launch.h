@@ -14,7 +14,6 @@ struct LaunchArgs {
     float tau;        // lazy-rescale threshold in log2 units (0 = raise the reference on every new maximum)
     uint32_t qsign;   // 0x80008000 when scale < 0 (sign folded into Q), else 0
     int linear_grid;
-    int wide;         // 64 query rows per wavefront (tile_m 128 = 2 x 64, 256 = 4 x 64) instead of 32
     hipStream_t stream;
 };
 

@@ -12,13 +12,7 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
-bool valid_tile(int tm, int tn, int D, bool wide)
-{
-    if (!(tm == 64 || tm == 128 || tm == 256) || !(tn == 32 || tn == 64 || tn == 128)) return false;
-    // every wavefront of the workgroup must get at least one 64-chunk load per tile
-    const int waves = tm == 64 ? 2 : (tm == 128 ? (wide ? 2 : 4) : (wide ? 4 : 8));
-    return tn * (D / 8) >= waves * 64;
-}
+bool valid_tile(int tm, int tn) { return (tm == 64 || tm == 128) && (tn == 32 || tn == 64 || tn == 128); }
 
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
 void pick_tile(int BH, int S, int D, int *tm, int *tn)
@@ -62,7 +56,7 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_BAD_DTYPE: return "bad dtype: expected TSDPA_F16 or TSDPA_BF16";
         case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64 or 128";
         case TSDPA_ERR_MISALIGNED: return "misaligned pointer: q, k, v, o need 16-byte, lse 4-byte alignment";
-        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128,256}, tile_n in {32,64,128}, or both 0";
+        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128}, or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
         default: return "unknown status";
@@ -90,7 +84,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     if (tile_m == 0 && tile_n == 0)
         pick_tile(B * H, S, D, &tile_m, &tile_n);
-    else if (!valid_tile(tile_m, tile_n, D, (flags & TSDPA_FLAG_WIDE_WAVES) != 0))
+    else if (!valid_tile(tile_m, tile_n))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
     if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
@@ -107,7 +101,6 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
     a.linear_grid = (flags & TSDPA_FLAG_LINEAR_GRID) ? 1 : 0;
-    a.wide = (flags & TSDPA_FLAG_WIDE_WAVES) ? 1 : 0;
     a.stream = (hipStream_t)stream;
 
     int err;
