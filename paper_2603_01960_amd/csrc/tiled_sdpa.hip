@@ -18,13 +18,13 @@ bool valid_tile(int tm, int tn) { return (tm == 64 || tm == 128) && (tn == 32 ||
 void pick_tile(int BH, int S, int D, int *tm, int *tn)
 {
     (void)BH;
-    // From the tile sweep on MI355X: 128 query rows per workgroup and 64-row K/V tiles (64 KB of LDS at
-    // D = 128, two workgroups per CU) win at every configuration measured.
-    *tm = 128;
-    *tn = 64;
     (void)D;
+    // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts, two workgroups per
+    // CU) wins at every configuration measured; 64-row K/V tiles for long sequences, 32-row tiles when
+    // there are only a few tiles per head, so the pipeline fills sooner and the ragged tail wastes less.
+    *tm = 128;
+    *tn = S >= 512 ? 64 : 32;
     if (S <= 64) *tm = 64;
-    if (S <= 32) *tn = 32;
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
