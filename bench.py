@@ -26,7 +26,12 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
 # scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    ("C4", "bf16"): 680.9e6,   # 546.7 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
+    ("C5", "f16"): 626.6e6,    # 559.5 MB + 67.1 MB          (profiles/sdpa_fwd_C5_f16.md)
+    ("C3", "bf16"): 77.6e6,    # 58.2 MB + 19.4 MB           (profiles/sdpa_fwd_C3_bf16.md)
+    ("C2", "f16"): 33.7e6,     # 25.4 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
+}
 
 # The paper's own figures, other hardware (NVIDIA DGX GB10): context only, never a target.
 PAPER_CONTEXT = {
@@ -49,6 +54,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run only a device-to-device copy of --copy-mib MiB (reference for the HBM byte counters)")
+    ap.add_argument("--copy-mib", type=int, default=1024)
     return ap.parse_args()
 
 
@@ -62,25 +70,65 @@ def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0):
     for _ in range(warmup):
         run()
     torch.cuda.synchronize()
-    starts = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
-    stops = [torch.cuda.Event(enable_timing=True) for _ in range(steps)]
+    # events go to the same (current) stream the kernel is enqueued on.  marks[i] precedes launch i and
+    # marks[steps] follows the last one: the region average is (last - first) / steps, and consecutive
+    # marks give the per-launch spread (for kernels of tens of microseconds each of those intervals
+    # also holds the launch gap, so the median / p95 are an upper bound there).
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     for i in range(steps):
-        starts[i].record()          # same (current) stream the kernel is enqueued on
+        marks[i].record()
         run()
-        stops[i].record()
+    marks[steps].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
-    per_launch_ms = sorted(s.elapsed_time(e) for s, e in zip(starts, stops))
+    per_launch_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    region_ms = marks[0].elapsed_time(marks[steps])
     assert torch.isfinite(o.float()).all().item(), "non-finite output"
     return {
         "workload": w, "dtype": dtype, "wall_s": wall,
         "ms_per_step": 1e3 * wall / steps,
-        "kernel_ms_avg": sum(per_launch_ms) / steps,
+        "kernel_ms_avg": region_ms / steps,
         "kernel_ms_median": statistics.median(per_launch_ms),
         "kernel_ms_p95": per_launch_ms[min(steps - 1, int(0.95 * steps))],
         "tensors": (q, k, v),
     }
+
+
+def time_batched(pkg, torch, name, dtype, n, warmup):
+    """Per-launch time with the launches issued back to back between ONE pair of events: for kernels
+    of a few tens of microseconds the event pair of time_workload() mostly measures launch latency."""
+    from paper_2603_01960_amd.workloads import make_workload
+    w, q, k, v = make_workload(name, dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    o = torch.empty_like(qd)
+    for _ in range(warmup):
+        pkg.sdpa(qd, kd, vd, out=o)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(n):
+        pkg.sdpa(qd, kd, vd, out=o)
+    b.record()
+    torch.cuda.synchronize()
+    return w, a.elapsed_time(b) / n
+
+
+def copy_calibration(torch, mib, steps):
+    """Plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales those counters."""
+    n = mib * (1 << 20)
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    ms = a.elapsed_time(b) / steps
+    print(json.dumps({"copy_bytes": n, "copies": steps, "ms_per_copy": round(ms, 4),
+                      "GBs_read_plus_write": round(2 * n / ms / 1e6, 1)}), flush=True)
 
 
 def cpu_baseline(w, q, k, v, target_seconds):
@@ -122,6 +170,9 @@ def main():
         sys.exit(3)
     pkg.load_library()      # no fallback: raises if the HIP library is not built
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        copy_calibration(torch, args.copy_mib, args.steps)
+        return
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else None
     flags = (pkg.binding.FLAG_LINEAR_GRID if args.linear_grid else 0) \
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0)
@@ -169,13 +220,11 @@ def main():
         others = {}
         for name, dts in (("C1", ["f16"]), ("C2", ["f16", "bf16"]), ("C3", ["bf16"]), ("C4", ["bf16"]), ("C5", ["f16"])):
             for dt in dts:
-                rr = time_workload(pkg, torch, name, dt, max(10, args.steps // 2), args.warmup)
-                ww = rr["workload"]
+                ww, ms = time_batched(pkg, torch, name, dt, max(20, args.steps), args.warmup)
                 others[f"{name}_{dt}"] = {
-                    "kernel_ms_median": round(rr["kernel_ms_median"], 5),
-                    "tflops": round(ww.flops / (rr["kernel_ms_median"] * 1e-3) / 1e12, 2),
-                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (rr["kernel_ms_median"] * 1e-3) / 1e9, 1)}
-                del rr
+                    "ms_per_launch_back_to_back": round(ms, 5),
+                    "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
+                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
         out["all_workloads"] = others
 
     if not args.no_cpu_baseline:
