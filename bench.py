@@ -54,16 +54,22 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only ceiling measurement")
+    ap.add_argument("--input-fill", default="normal", choices=["normal", "zeros", "ones"],
+                    help="normal = the seeded workload; zeros / ones = same shapes with constant data "
+                         "(clock experiment: the same instruction stream at lower switching activity)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of --copy-mib MiB (reference for the HBM byte counters)")
     ap.add_argument("--copy-mib", type=int, default=1024)
     return ap.parse_args()
 
 
-def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0):
+def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal"):
     from paper_2603_01960_amd.workloads import make_workload
     w, q, k, v = make_workload(name, dtype)
     dtype = dtype or w.dtypes[0]
+    if fill != "normal":
+        q, k, v = (torch.zeros_like(t) if fill == "zeros" else torch.ones_like(t) for t in (q, k, v))
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     o = torch.empty_like(qd)
     run = lambda: pkg.sdpa(qd, kd, vd, out=o, tile=tile, flags=flags)
@@ -114,6 +120,26 @@ def time_batched(pkg, torch, name, dtype, n, warmup):
     return w, a.elapsed_time(b) / n
 
 
+def mfma_ceilings(pkg, torch, dtype, iters=4000):
+    """What a register-resident MFMA stream sustains on this GPU right now (TFLOP/s), with random and
+    with constant operand data; the gap is the clock the chip gives up to its power limit."""
+    sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    code = pkg.F16 if dtype == "f16" else pkg.BF16
+    out = {}
+    for label, rnd in (("random_operands", True), ("constant_operands", False)):
+        for _ in range(2):
+            pkg.probe_mfma(code, rnd, iters, sink.data_ptr(), stream)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        flops = sum(pkg.probe_mfma(code, rnd, iters, sink.data_ptr(), stream) for _ in range(3))
+        b.record()
+        torch.cuda.synchronize()
+        out[label] = round(flops / (a.elapsed_time(b) * 1e-3) / 1e12, 1)
+    return out
+
+
 def copy_calibration(torch, mib, steps):
     """Plain copy of known size: what FETCH_SIZE / WRITE_SIZE read for it scales those counters."""
     n = mib * (1 << 20)
@@ -141,8 +167,7 @@ def cpu_baseline(w, q, k, v, target_seconds):
     sdpa_oracle.sdpa(qn, kn, vn, rows=probe)
     dt = max(time.perf_counter() - t, 1e-4)
     nrows = int(min(w.S, max(len(probe), len(probe) * target_seconds / dt)))
-    stride = max(1, w.S // nrows)
-    rows = list(range(0, w.S, stride))[:nrows]
+    rows = sorted({(i * w.S) // nrows for i in range(nrows)})      # evenly spread over the sequence
     t = time.perf_counter()
     sdpa_oracle.sdpa(qn, kn, vn, rows=rows)
     dt = time.perf_counter() - t
@@ -150,7 +175,7 @@ def cpu_baseline(w, q, k, v, target_seconds):
     return {
         "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": sdpa_oracle.num_threads(),
         "kind": "oracle", "seconds": round(dt, 3),
-        "sample": f"{w.name}: all {w.BH} heads x {len(rows)} of {w.S} query rows (stride {stride}) "
+        "sample": f"{w.name}: all {w.BH} heads x {len(rows)} of {w.S} query rows (evenly spaced) "
                   f"against all {w.S} keys, float64",
     }
 
@@ -177,7 +202,7 @@ def main():
     flags = (pkg.binding.FLAG_LINEAR_GRID if args.linear_grid else 0) \
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0)
 
-    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags)
+    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill)
     w, dtype = r["workload"], r["dtype"]
     tflops = w.flops / (r["ms_per_step"] * 1e-3) / 1e12
     kern_tflops = w.flops / (r["kernel_ms_avg"] * 1e-3) / 1e12
@@ -205,7 +230,8 @@ def main():
         "metric": "SDPA forward TFLOP/s (4*B*H*S^2*D / t)", "value": round(tflops, 2), "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "vs_baseline": None, "dtype": dtype,
+        "data": "synthetic" if args.input_fill == "normal" else f"constant {args.input_fill} (clock experiment)",
         "config": {"workload": f"{w.name}: SDPA fwd non-causal B={w.B} H={w.H} S={w.S} D={w.D} {dtype}",
                    "tile_m": tm, "tile_n": tn, "seed": w.seed, "qk_std": round(w.qk_std, 6),
                    "tokens_per_s": round(w.BH * w.S / (r["ms_per_step"] * 1e-3), 1)},
@@ -215,6 +241,11 @@ def main():
         "env": {"torch": torch.__version__, "hip": torch.version.hip, "device": torch.cuda.get_device_name(0),
                 "library_version": pkg.version(), "host": platform.processor() or platform.machine()},
     }
+
+    if not args.no_ceilings:
+        ceil = mfma_ceilings(pkg, torch, dtype)
+        out["mfma_only_ceiling_tflops"] = ceil
+        out["frac_of_mfma_only_ceiling_random_operands"] = round(kern_tflops / ceil["random_operands"], 4)
 
     if args.all_workloads:
         others = {}

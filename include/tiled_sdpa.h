@@ -84,6 +84,20 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
 /* The (tile_m, tile_n) the heuristic picks for a shape; returns a status code. */
 int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, int *tile_m, int *tile_n);
 
+/*
+ * Measurement aid, not part of the attention path: enqueue a register-resident stream of
+ * v_mfma_f32_32x32x16 (FP16 or BF16 per `dtype`) on every SIMD of the GPU -- 512 workgroups of four
+ * wavefronts, `iters` x 64 MFMAs per wavefront -- so the caller can time what the matrix pipe
+ * sustains with no memory traffic.  random_operands != 0 fills the operand registers with random
+ * signs and mantissas (the switching activity of real data, under which the chip lowers its
+ * clock); 0 uses constant ones.  sink: device buffer of at least 512*256 floats, overwritten.
+ * flops (host pointer, may be NULL) receives the flop count of the launch.  The Section 4.2.3
+ * policy of measuring on an otherwise idle GPU applies.  Returns a status code; iters = 0 only
+ * reports flops.
+ */
+int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink, double *flops,
+                          void *stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char *tiled_sdpa_status_string(int status);
 

@@ -22,6 +22,7 @@ EXPORTS = (
     "tiled_sdpa_fwd",
     "tiled_sdpa_fwd_ex",
     "tiled_sdpa_default_tile",
+    "tiled_sdpa_probe_mfma",
     "tiled_sdpa_status_string",
     "tiled_sdpa_version",
 )
@@ -54,6 +55,8 @@ def load_library():
     lib.tiled_sdpa_fwd_ex.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint]
     lib.tiled_sdpa_default_tile.restype = ci
     lib.tiled_sdpa_default_tile.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.tiled_sdpa_probe_mfma.restype = ci
+    lib.tiled_sdpa_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tiled_sdpa_status_string.restype = ctypes.c_char_p
     lib.tiled_sdpa_status_string.argtypes = [ci]
     lib.tiled_sdpa_version.restype = ci
@@ -76,6 +79,18 @@ def default_tile(B: int, H: int, S: int, D: int, dtype: int):
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return tm.value, tn.value
+
+
+def probe_mfma(dtype: int, random_operands: bool, iters: int, sink=None, stream=None) -> float:
+    """Enqueue the MFMA-only stream (see tiled_sdpa_probe_mfma); returns its flop count.
+
+    With ``sink=None`` and ``iters=0`` nothing is launched (flop count only)."""
+    flops = ctypes.c_double(0.0)
+    st = load_library().tiled_sdpa_probe_mfma(dtype, 1 if random_operands else 0, iters,
+                                              sink if sink is not None else 0x1000, ctypes.byref(flops), stream)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return flops.value
 
 
 def tiled_sdpa_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype, stream) -> int:

@@ -1,0 +1,87 @@
+// Measurement aids: what the matrix pipe of this GPU sustains with nothing else in the way.
+// The attention kernel is judged against the published dense MFMA peak; these loops show how much of
+// that peak a pure register-resident MFMA stream reaches, and how much the operand DATA matters:
+// with random mantissas and signs the chip runs into its power limit and lowers the shader clock,
+// with constant operands it does not.  See include/tiled_sdpa.h (tiled_sdpa_probe_mfma).
+#include "tiled_sdpa.h"
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kGrid = 512;          // two workgroups of four wavefronts per CU: two wavefronts per SIMD
+constexpr int kMfmaPerIter = 64;    // fully unrolled body
+
+__device__ __forceinline__ uint32_t mix(uint32_t x)
+{
+    x ^= x >> 16; x *= 0x7feb352dU; x ^= x >> 15; x *= 0x846ca68bU; x ^= x >> 16;
+    return x;
+}
+
+template <bool BF16>
+__global__ void __launch_bounds__(256) mfma_stream(float *sink, int iters, int random_operands)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    // eight A and eight B fragments per lane; exponent fields fixed so nothing overflows
+    u32x4 ra[8], rb[8];
+    const uint32_t expo = BF16 ? 0x3f003f00u : 0x38003800u;
+    const uint32_t keep = BF16 ? 0x807f807fu : 0x83ff83ffu;
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t h = mix((blockIdx.x * 256u + threadIdx.x) * 64u + f * 8u + e);
+            ra[f][e] = random_operands ? ((h & keep) | expo) : (BF16 ? 0x3f803f80u : 0x3c003c00u);
+            rb[f][e] = random_operands ? ((mix(h) & keep) | expo) : (BF16 ? 0x3f803f80u : 0x3c003c00u);
+        }
+    f32x16 acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                if constexpr (BF16)
+                    acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ra[f]),
+                                                                        __builtin_bit_cast(bf16x8, rb[(f + u) & 7]),
+                                                                        acc[f & 3], 0, 0, 0);
+                else
+                    acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, ra[f]),
+                                                                       __builtin_bit_cast(f16x8, rb[(f + u) & 7]),
+                                                                       acc[f & 3], 0, 0, 0);
+            }
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[n][i];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+#endif
+}
+
+}  // namespace
+
+extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink,
+                                     double *flops, void *stream)
+{
+    if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
+    if (iters < 0) return TSDPA_ERR_BAD_SHAPE;
+    if (!sink) return TSDPA_ERR_NULL_PTR;
+    if (flops) *flops = (double)kGrid * 4.0 * (double)iters * kMfmaPerIter * 32768.0;
+    if (iters == 0) return TSDPA_OK;
+    if (dtype == TSDPA_BF16)
+        hipLaunchKernelGGL(mfma_stream<true>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
+    else
+        hipLaunchKernelGGL(mfma_stream<false>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
+    return hipGetLastError() == hipSuccess ? TSDPA_OK : TSDPA_ERR_LAUNCH;
+}
