@@ -90,6 +90,17 @@ def test_plain_entry_point_validates_too(lib):
     assert binding.tiled_sdpa_fwd(None, None, None, None, None, 0, 4, 16, 64, 0.125, 1, None) == OK
 
 
+def test_probe_validates_before_touching_the_gpu(lib):
+    import ctypes
+    fl = ctypes.c_double(-1.0)
+    assert lib.tiled_sdpa_probe_mfma(5, 0, 10, P, ctypes.byref(fl), None) == DTYPE
+    assert lib.tiled_sdpa_probe_mfma(0, 0, -1, P, ctypes.byref(fl), None) == SHAPE
+    assert lib.tiled_sdpa_probe_mfma(0, 0, 10, None, ctypes.byref(fl), None) == NULL
+    assert lib.tiled_sdpa_probe_mfma(1, 1, 0, P, ctypes.byref(fl), None) == OK     # iters = 0: flops only
+    assert fl.value == 0.0
+    assert binding.probe_mfma(binding.BF16, True, 0) == 0.0
+
+
 def test_default_tile_is_a_legal_tile(lib):
     for S in (1, 32, 64, 197, 1024, 16384):
         for D in (64, 128):

@@ -166,6 +166,30 @@ def test_linear_grid_flag_gives_identical_bits():
     assert torch.equal(a, b)
 
 
+def test_exact_max_flag_matches_the_oracle_and_the_default():
+    """tau = 0 (Eq. 2 literally) and the lazy reference give the same result up to rounding."""
+    for dtype, D in (("f16", 64), ("bf16", 128)):
+        q, k, v = make_qkv(1, 3, 700, D, dtype, seed=81, qk_std=1.5)
+        a = check(q, k, v, dtype, flags=binding.FLAG_EXACT_MAX, tag="exact max")
+        b = check(q, k, v, dtype, tag="lazy reference")
+        assert abs(a - b) <= TOL[dtype]
+
+
+def test_mfma_probe_runs_and_reports_its_flops():
+    sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for dt in (binding.F16, binding.BF16):
+        for rnd in (False, True):
+            flops = binding.probe_mfma(dt, rnd, 10, sink.data_ptr(), stream)
+            torch.cuda.synchronize()
+            assert flops == 512 * 4 * 10 * 64 * 32768
+            assert torch.isfinite(sink).all()
+    # constant operands: every accumulator element is 16 (ones . ones over k = 16) per MFMA
+    binding.probe_mfma(binding.BF16, False, 1, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert float(sink[0]) == 64 * 16 * 16      # 64 MFMAs x 16 accumulator elements summed x 16
+
+
 # ------------------------------------------------------------------ the five configurations
 def test_config_C1_full():
     w, q, k, v = make_workload("C1")
