@@ -3,10 +3,13 @@
  * it exists to check the HIP path, shares no code with it, and must never be
  * called from the product path.
  *
- * What it computes is the plain definition of the paper's Eq. 1 (Section 3.1)
- * with the mask M = 0, written out row by row in float64:
+ * What it computes is the plain definition of the paper's Eq. 1 (Section 3.1),
+ * written out row by row in float64, with the mask M = 0 or, when `causal` is
+ * set, the causal mask of Section 4.1.3 (M_ij = 0 for j <= i, -inf for j > i:
+ * keys after the query contribute nothing), which simply shortens the sums to
+ * j = 0..i:
  *
- *     s_ij  = scale * sum_d q_id * k_jd          (j = 0..S-1)
+ *     s_ij  = scale * sum_d q_id * k_jd          (j = 0..S-1, or 0..i if causal)
  *     M_i   = max_j s_ij
  *     e_ij  = exp(s_ij - M_i)
  *     L_i   = sum_j e_ij
@@ -25,7 +28,7 @@
  * [BH,S,D]).  `rows` selects query rows (same subset for every bh); NULL means
  * all S rows.  Outputs: o [BH, nrows, D] double, lse [BH, nrows] double
  * (nullable), p [BH, nrows, S] double (nullable; the softmax probabilities
- * e_ij / L_i, exposed for the rows-sum-to-one pin).
+ * e_ij / L_i, zero for masked keys, exposed for the rows-sum-to-one pin).
  *
  * Returns 0, or a negative number for bad arguments / allocation failure.
  */
@@ -46,7 +49,7 @@ int sdpa_oracle_num_threads(void)
 
 int sdpa_oracle_rows(const float *q, const float *k, const float *v,
                      long BH, long S, long D, double scale,
-                     const long *rows, long nrows,
+                     const long *rows, long nrows, int causal,
                      double *o, double *lse, double *p)
 {
     if (!q || !k || !v || !o) return -1;
@@ -77,9 +80,10 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
             const float *kb = k + bh * S * D;
             const float *vb = v + bh * S * D;
 
-            /* scores and their maximum */
+            /* scores and their maximum; masked keys (j > i under the causal mask) are left out */
+            const long J = causal ? i + 1 : S;
             double M = -INFINITY;
-            for (long j = 0; j < S; ++j) {
+            for (long j = 0; j < J; ++j) {
                 const float *kj = kb + j * D;
                 double dot = 0.0;
                 for (long d = 0; d < D; ++d) dot += (double)qi[d] * (double)kj[d];
@@ -89,7 +93,7 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
             /* exponentials, normaliser, weighted sum of value rows */
             double L = 0.0;
             for (long d = 0; d < D; ++d) acc[d] = 0.0;
-            for (long j = 0; j < S; ++j) {
+            for (long j = 0; j < J; ++j) {
                 const double e = exp(s[j] - M);
                 s[j] = e;
                 L += e;
@@ -101,7 +105,7 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
             if (lse) lse[t] = M + log(L);
             if (p) {
                 double *pi = p + t * S;
-                for (long j = 0; j < S; ++j) pi[j] = s[j] / L;
+                for (long j = 0; j < S; ++j) pi[j] = j < J ? s[j] / L : 0.0;
             }
         }
         free(s);

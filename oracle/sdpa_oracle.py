@@ -54,7 +54,7 @@ def _load():
         lib.sdpa_oracle_rows.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
-            ctypes.c_void_p, ctypes.c_long,
+            ctypes.c_void_p, ctypes.c_long, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.sdpa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -76,8 +76,9 @@ def _as_f32(x) -> np.ndarray:
     return a32
 
 
-def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False):
-    """Materialised float64 attention, Eq. 1 (Section 3.1) with M = 0.
+def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False, causal=False):
+    """Materialised float64 attention, Eq. 1 (Section 3.1) with M = 0, or with the causal mask of
+    Section 4.1.3 (keys after the query are left out) when ``causal`` is set.
 
     q, k, v: arrays of shape [..., S, D] (leading dims are batch/head and must
     agree).  scale: defaults to 1/sqrt(D) (Section 4.2.1); if given it is used
@@ -106,7 +107,7 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False):
     p = np.empty((BH, nrows, S), dtype=np.float64) if return_p else None
     rc = _load().sdpa_oracle_rows(
         q32.ctypes.data, k32.ctypes.data, v32.ctypes.data, BH, S, D, scale,
-        rows_ptr, nrows, o.ctypes.data,
+        rows_ptr, nrows, 1 if causal else 0, o.ctypes.data,
         lse.ctypes.data if lse is not None else None,
         p.ctypes.data if p is not None else None)
     if rc != 0:
@@ -119,8 +120,9 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False):
     return out[0] if len(out) == 1 else tuple(out)
 
 
-def sdpa_numpy(q, k, v, scale=None, return_lse=False):
-    """Eq. 1 (Section 3.1), M = 0, as numpy float64 matrix expressions."""
+def sdpa_numpy(q, k, v, scale=None, return_lse=False, causal=False):
+    """Eq. 1 (Section 3.1) as numpy float64 matrix expressions; M = 0, or the causal mask
+    (M_ij = -inf for j > i, Section 4.1.3) added to the scaled scores exactly as Eq. 1 writes it."""
     q64 = np.asarray(q, dtype=np.float64)
     k64 = np.asarray(k, dtype=np.float64)
     v64 = np.asarray(v, dtype=np.float64)
@@ -129,6 +131,9 @@ def sdpa_numpy(q, k, v, scale=None, return_lse=False):
         scale = 1.0 / np.sqrt(np.float64(D))
     scale = float(np.float32(scale))
     s = scale * (q64 @ np.swapaxes(k64, -1, -2))
+    if causal:
+        S = s.shape[-1]
+        s = s + np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, 0.0)
     m = s.max(axis=-1, keepdims=True)
     e = np.exp(s - m)
     L = e.sum(axis=-1, keepdims=True)
@@ -138,7 +143,7 @@ def sdpa_numpy(q, k, v, scale=None, return_lse=False):
     return o
 
 
-def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False):
+def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False, causal=False):
     """Blockwise online-softmax attention, Section 4.1.2 (Eqs. 2-4), in float64.
 
     One [S, D] problem.  ``tile_bounds`` is an increasing list of key indices
@@ -147,6 +152,8 @@ def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False):
     output accumulator (Eq. 4); after the last tile O_i = o_i / l_i.  The state
     starts at m = -inf, l = 0, o = 0 (the paper does not state the start; any
     start with l = 0, o = 0 and m below every score gives the same result).
+    With ``causal`` the scores of keys after the query are set to -inf before the
+    update (a row whose keys in a tile are all masked keeps its state).
     """
     q64 = np.asarray(q, dtype=np.float64)
     k64 = np.asarray(k, dtype=np.float64)
@@ -162,10 +169,13 @@ def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False):
     o = np.zeros((S, D))
     for lo, hi in zip(tile_bounds[:-1], tile_bounds[1:]):
         s_tile = scale * (q64 @ k64[lo:hi].T)                    # S_ij for this tile
+        if causal:                                               # mask, then update (Section 4.1.2)
+            s_tile = np.where(np.arange(lo, hi)[None, :] > np.arange(S)[:, None], -np.inf, s_tile)
         m_old = m
         m = np.maximum(m_old, s_tile.max(axis=1))                # Eq. 2
-        alpha = np.exp(m_old - m)                                # e^{m_old - m}
-        e = np.exp(s_tile - m[:, None])
+        with np.errstate(invalid="ignore"):
+            alpha = np.where(np.isneginf(m), 0.0, np.exp(m_old - m))   # e^{m_old - m}; rows with no key yet
+            e = np.where(np.isneginf(s_tile), 0.0, np.exp(s_tile - m[:, None]))
         l = l * alpha + e.sum(axis=1)                            # Eq. 3
         o = o * alpha[:, None] + e @ v64[lo:hi]                  # Eq. 4
     out = o / l[:, None]

@@ -40,6 +40,7 @@ def load_golden(name):
     assert fields["scale_is"] == "ln2"
     g = {
         "S": S, "D": D, "scale": LN2_F32, "tol": float(fields["tol"]),
+        "causal": fields.get("mask", "none") == "causal",
         "Q": np.array(_parse_matrix(fields["Q"])), "K": np.array(_parse_matrix(fields["K"])),
         "V": np.array(_parse_matrix(fields["V"])),
         "O": np.array(_parse_matrix(fields["O"], lambda t: float(Fraction(t)))),
@@ -50,7 +51,7 @@ def load_golden(name):
     return g
 
 
-GOLDEN_FILES = ["pow2_softmax.txt", "two_key_sigmoid.txt"]
+GOLDEN_FILES = ["pow2_softmax.txt", "two_key_sigmoid.txt", "pow2_softmax_causal.txt"]
 
 
 def _rand(shape, seed, dtype=np.float16, std=1.0):
@@ -69,14 +70,15 @@ def _bf16_round(x):
 def test_golden_rational_examples(name, impl):
     g = load_golden(name)
     q, k, v = (g[x].astype(np.float32) for x in "QKV")
+    cz = g["causal"]
     if impl == "c":
-        o, lse, p = orc.sdpa(q, k, v, scale=g["scale"], return_lse=True, return_p=True)
+        o, lse, p = orc.sdpa(q, k, v, scale=g["scale"], return_lse=True, return_p=True, causal=cz)
         np.testing.assert_allclose(p, g["P"], atol=g["tol"], rtol=0)
     elif impl == "numpy":
-        o, lse = orc.sdpa_numpy(q, k, v, scale=g["scale"], return_lse=True)
+        o, lse = orc.sdpa_numpy(q, k, v, scale=g["scale"], return_lse=True, causal=cz)
     else:
         o, lse = orc.sdpa_online(q, k, v, scale=g["scale"],
-                                 tile_bounds=list(range(g["S"] + 1)), return_lse=True)
+                                 tile_bounds=list(range(g["S"] + 1)), return_lse=True, causal=cz)
     np.testing.assert_allclose(o, g["O"], atol=g["tol"], rtol=0)
     np.testing.assert_allclose(lse, g["LSE"], atol=g["tol"], rtol=0)
 
@@ -320,6 +322,8 @@ def _pin_suite(fn):
 
     for gname in GOLDEN_FILES:
         g = load_golden(gname)
+        if g["causal"]:
+            continue            # the causal fixtures have their own suite below
         o, lse = fn(g["Q"], g["K"], g["V"], g["scale"])
         check("golden-o:" + gname, np.allclose(o, g["O"], atol=g["tol"], rtol=0))
         check("golden-lse:" + gname, np.allclose(lse, g["LSE"], atol=g["tol"], rtol=0))
@@ -375,3 +379,75 @@ def test_pins_pass_on_the_oracle_and_catch_planted_mistakes():
     for name, kw in mutants.items():
         bad = _pin_suite(lambda q, k, v, s, kw=kw: _definition(q, k, v, float(np.float32(s)), **kw))
         assert bad, f"planted mistake not caught: {name}"
+
+
+# ------------------------------------------------------------------ causal mask (Section 4.1.3)
+def test_causal_row_i_equals_plain_attention_over_the_first_i_plus_one_keys():
+    """Eq. 1 with the causal mask: row i attends keys 0..i, i.e. the unmasked problem truncated at i."""
+    q, k, v = (_rand((2, 41, 16), 500 + i, std=1.5) for i in range(3))
+    o, lse, p = orc.sdpa(q, k, v, causal=True, return_lse=True, return_p=True)
+    assert np.array_equal(o[:, 0], v[:, 0].astype(np.float64))          # first row: its own value row
+    np.testing.assert_allclose(p.sum(-1), 1.0, atol=1e-13)
+    assert np.all(np.triu(p, k=1) == 0)                                  # nothing after the query
+    for i in (0, 1, 7, 20, 40):
+        # plain attention of query i over keys 0..i, written out with numpy
+        for b in range(2):
+            s = float(np.float32(1 / math.sqrt(16))) * (k[b, :i + 1].astype(np.float64) @ q[b, i].astype(np.float64))
+            w = np.exp(s - s.max())
+            ref = (w[:, None] * v[b, :i + 1].astype(np.float64)).sum(0) / w.sum()
+            np.testing.assert_allclose(o[b, i], ref, atol=1e-13)
+            np.testing.assert_allclose(lse[b, i], s.max() + math.log(w.sum()), atol=1e-13)
+
+
+def test_causal_against_torch_float64_and_numpy_and_online():
+    q, k, v = (_rand((2, 3, 150, 64), 510 + i, std=1.3) for i in range(3))
+    o, lse = orc.sdpa(q, k, v, causal=True, return_lse=True)
+    tq, tk, tv = (torch.from_numpy(x.astype(np.float64)) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=0.125).numpy()
+    np.testing.assert_allclose(o, ref, atol=1e-12, rtol=0)
+    o_np, lse_np = orc.sdpa_numpy(q, k, v, causal=True, return_lse=True)
+    np.testing.assert_allclose(o, o_np, atol=1e-13, rtol=0)
+    np.testing.assert_allclose(lse, lse_np, atol=1e-13, rtol=0)
+    o_on, lse_on = orc.sdpa_online(q[0, 0], k[0, 0], v[0, 0], causal=True, return_lse=True,
+                                   tile_bounds=[0, 7, 64, 65, 128, 150])
+    np.testing.assert_allclose(o_on, o[0, 0], atol=1e-12, rtol=0)
+    np.testing.assert_allclose(lse_on, lse[0, 0], atol=1e-12, rtol=0)
+
+
+def test_causal_output_ignores_later_keys_and_values():
+    q, k, v = (_rand((33, 8), 520 + i) for i in range(3))
+    o1 = orc.sdpa(q, k, v, causal=True)
+    k2, v2 = k.copy(), v.copy()
+    k2[20:] += 3
+    v2[20:] -= 5
+    o2 = orc.sdpa(q, k2, v2, causal=True)
+    assert np.array_equal(o1[:20], o2[:20])
+    assert np.abs(o1[20:] - o2[20:]).max() > 1e-2
+    rows = [0, 5, 32]
+    assert np.array_equal(orc.sdpa(q, k, v, causal=True, rows=rows), o1[rows])
+
+
+def test_causal_pins_catch_planted_mask_mistakes():
+    g = load_golden("pow2_softmax_causal.txt")
+    q, k, v = (_rand((19, 8), 530 + i) for i in range(3))
+    tq, tk, tv = (torch.from_numpy(x.astype(np.float64)) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True).numpy()
+
+    def masked(qq, kk, vv, scale, keep):
+        qq, kk, vv = (np.asarray(x, np.float64) for x in (qq, kk, vv))
+        s = scale * (qq @ kk.T)
+        n = s.shape[0]
+        s = np.where(keep(np.arange(n)[:, None], np.arange(n)[None, :]), s, -np.inf)
+        w = np.exp(s - s.max(-1, keepdims=True))
+        return (w @ vv) / w.sum(-1, keepdims=True)
+
+    def fails(keep):
+        bad = not np.allclose(masked(g["Q"], g["K"], g["V"], g["scale"], keep), g["O"], atol=g["tol"])
+        bad |= not np.allclose(masked(q, k, v, float(np.float32(8 ** -0.5)), keep), ref, atol=1e-12)
+        return bad
+
+    assert not fails(lambda i, j: j <= i)                       # the right mask passes
+    assert fails(lambda i, j: j <= i + 1)                       # diagonal off by one (too wide)
+    assert fails(lambda i, j: (j < i) | (i == 0))               # diagonal off by one (too narrow)
+    assert fails(lambda i, j: j >= i)                           # mask transposed
+    assert fails(lambda i, j: j == j)                           # no mask
