@@ -51,6 +51,8 @@ def parse_args():
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
+    ap.add_argument("--causal", action="store_true",
+                    help="causal mask (Section 4.1.3); flops are then counted as half of the non-causal figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
@@ -200,30 +202,32 @@ def main():
         return
     tile = tuple(int(x) for x in args.tile.split(",")) if args.tile else None
     flags = (pkg.binding.FLAG_LINEAR_GRID if args.linear_grid else 0) \
-        | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0)
+        | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0) \
+        | (pkg.binding.FLAG_CAUSAL if args.causal else 0)
 
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill)
     w, dtype = r["workload"], r["dtype"]
-    tflops = w.flops / (r["ms_per_step"] * 1e-3) / 1e12
-    kern_tflops = w.flops / (r["kernel_ms_avg"] * 1e-3) / 1e12
+    flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
+    tflops = flops / (r["ms_per_step"] * 1e-3) / 1e12
+    kern_tflops = flops / (r["kernel_ms_avg"] * 1e-3) / 1e12
     tm, tn = tile if tile else pkg.binding.default_tile(w.B, w.H, w.S, w.D, pkg.F16 if dtype == "f16" else pkg.BF16)
 
     # which roof bounds the kernel: arithmetic intensity on compulsory bytes vs the ridge point
     comp_bytes = w.compulsory_bytes(2)
     ridge = PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    if w.flops / comp_bytes >= ridge:
+    if flops / comp_bytes >= ridge:
         roofline = {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_MFMA_TFLOPS,
                     "unit": "TFLOP/s", "frac": round(kern_tflops / PEAK_MFMA_TFLOPS, 4)}
     else:
         gbs = comp_bytes / (r["kernel_ms_avg"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4)}
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dtype))
+    roofline["traffic"] = None if args.causal else MEASURED_TRAFFIC_BYTES.get((w.name, dtype))
     roofline["kernel"] = f"sdpa_fwd_kernel<{dtype},D={w.D},T_M={tm},T_N={tn}>"
     roofline["kernel_ms_avg"] = round(r["kernel_ms_avg"], 5)
     roofline["kernel_ms_median"] = round(r["kernel_ms_median"], 5)
     roofline["kernel_ms_p95"] = round(r["kernel_ms_p95"], 5)
-    roofline["algorithmic_flops_per_launch"] = w.flops
+    roofline["algorithmic_flops_per_launch"] = flops
     roofline["compulsory_hbm_bytes_per_launch"] = comp_bytes
 
     out = {
@@ -232,7 +236,8 @@ def main():
         "ms_per_step": round(r["ms_per_step"], 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": dtype,
         "data": "synthetic" if args.input_fill == "normal" else f"constant {args.input_fill} (clock experiment)",
-        "config": {"workload": f"{w.name}: SDPA fwd non-causal B={w.B} H={w.H} S={w.S} D={w.D} {dtype}",
+        "config": {"workload": f"{w.name}: SDPA fwd {'causal' if args.causal else 'non-causal'} "
+                               f"B={w.B} H={w.H} S={w.S} D={w.D} {dtype}",
                    "tile_m": tm, "tile_n": tn, "seed": w.seed, "qk_std": round(w.qk_std, 6),
                    "tokens_per_s": round(w.BH * w.S / (r["ms_per_step"] * 1e-3), 1)},
         "roofline": roofline,

@@ -12,7 +12,7 @@
  * memory.  Numerics follow Section 4.1.3: FP16 or BF16 inputs and output, FP32
  * accumulation of the dot products, the softmax statistics and the output.
  * The call surface mirrors the functional API of Section 4.2.1,
- * sdpa(q, k, v, causal, scale) -> o, restricted to causal = false.
+ * sdpa(q, k, v, causal, scale) -> o; causal = true is TSDPA_FLAG_CAUSAL of tiled_sdpa_fwd_ex.
  *
  * All pointers are DEVICE pointers owned by the caller.  The library allocates
  * and frees nothing, keeps no state besides its kernel table, never
@@ -44,10 +44,13 @@ enum {
 /* flags for tiled_sdpa_fwd_ex */
 enum {
     TSDPA_FLAG_LINEAR_GRID = 1u, /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
-    TSDPA_FLAG_EXACT_MAX = 2u    /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
+    TSDPA_FLAG_EXACT_MAX = 2u,   /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
                                     Default: raise it only when the tile maximum exceeds it by more than
                                     2^8, which gives the same O and lse up to rounding and skips most
                                     rescales of the accumulator. */
+    TSDPA_FLAG_CAUSAL = 8u       /* causal mask (Section 4.1.3; Eq. 1 with M_ij = -inf for j > i): key j
+                                    contributes to query row i only if j <= i.  K/V tiles strictly above
+                                    the diagonal of a workgroup's rows are neither read nor computed. */
 };
 
 /*

@@ -13,6 +13,7 @@ from pathlib import Path
 F16, BF16 = 0, 1
 FLAG_LINEAR_GRID = 1
 FLAG_EXACT_MAX = 2
+FLAG_CAUSAL = 8
 
 _PKG = Path(__file__).resolve().parent
 _LIB_PATH = _PKG / "libtiled_sdpa.so"
@@ -107,7 +108,7 @@ def tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dt
 
 def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False, out=None,
          lse_out=None, tile=None, flags: int = 0):
-    """o = softmax(q k^T * scale) v for contiguous [B, H, S, D] FP16/BF16 device tensors.
+    """o = softmax(q k^T * scale [+ causal mask]) v for contiguous [B, H, S, D] FP16/BF16 device tensors.
 
     Mirrors the functional API of Section 4.2.1 of the paper (scale defaults to 1/sqrt(D)).
     ``tile=(T_M, T_N)`` pins the schedule; ``out`` / ``lse_out`` let the caller own the outputs.
@@ -115,7 +116,7 @@ def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False,
     import torch
 
     if causal:
-        raise NotImplementedError("causal masking is not part of this build")
+        flags |= FLAG_CAUSAL
     for name, t in (("q", q), ("k", k), ("v", v)):
         if not isinstance(t, torch.Tensor) or not t.is_cuda:
             raise ValueError(f"{name} must be a device tensor")

@@ -34,7 +34,7 @@ int launch_one(const LaunchArgs &a)
     const int N = a.BH * nQ;
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
-                       a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid);
+                       a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal);
     return (int)hipGetLastError();
 }
 

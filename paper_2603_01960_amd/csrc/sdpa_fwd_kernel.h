@@ -114,7 +114,7 @@ template <typename T, int D, int NW, int TN, int WPS>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
-                float tau, uint32_t qsign, int linear_grid)
+                float tau, uint32_t qsign, int linear_grid, int causal)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     using E = Elem<T>;
@@ -135,7 +135,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const int g = lane >> 5, l32 = lane & 31;
 
     const int wg = remap_workgroup(blockIdx.x, N, linear_grid != 0);
-    const int head = wg / nQ, qt = wg - head * nQ;
+    const int head = wg / nQ;
+    // under the causal mask the work of a query tile grows with its index: start the long ones first
+    const int qt = causal ? nQ - 1 - (wg - head * nQ) : wg - head * nQ;
     const size_t head_off = (size_t)head * (size_t)S * D;
     const T *qh = q + head_off;
 
@@ -150,7 +152,16 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         qf[kk] = __builtin_bit_cast(vec8, raw);
     }
 
+    // Tiles this workgroup streams, and how many leading ones need no mask for any of its rows.
+    // A key j contributes to query row i iff j <= klim(i): klim = S-1 (only the ragged tail is cut
+    // off), or min(i, S-1) under the causal mask of Section 4.1.3, where tiles strictly above the
+    // diagonal of the workgroup's last row are neither read nor computed.
     const int nT = (S + TN - 1) / TN;
+    const int r0 = qt * TM;
+    const int last_row = (r0 + TM < S ? r0 + TM : S) - 1;
+    const int nTw = causal ? last_row / TN + 1 : nT;
+    const int klim = causal ? (qrow < S ? qrow : S - 1) : S - 1;
+    const int nfull = ((causal ? (r0 < S - 1 ? r0 : S - 1) : S - 1) + 1) / TN;
 
     // ---- K/V tiles: HBM -> LDS.  One buffer descriptor per tensor covers exactly this head's S rows,
     // so a row index >= S reads as zeros instead of touching memory.  Load instruction `it` of this
@@ -167,7 +178,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         v_goff[it] = r * G::ROW + ((cp ^ (G::vswz(r) << 2)) << 4);
     }
     auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) {
-        const int soff = j * G::TILE;     // wavefront-uniform; rows >= S fall outside the descriptor
+        // wavefront-uniform offset; rows >= S fall outside the descriptor and read as zeros without a
+        // memory access, and so does a tile this workgroup does not need (index moved past the end)
+        const int soff = (j < nTw ? j : nT) * G::TILE;
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
@@ -218,15 +231,15 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // Eq. 2 on one tile of scores: tile maximum, reference update and (rarely) the rescale of Eqs. 3-4.
     // Kept apart from the exponentials because it ends in a branch: everything after it (scores of the
     // next tile, exponentials, PV product) then forms one straight-line block the scheduler can interleave.
-    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
+    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
-        if constexpr (TAIL) {
+        if constexpr (MASK) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) >= S) sacc[nb][i] = -INFINITY;
+                    if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) > klim) sacc[nb][i] = -INFINITY;
         }
         float mx = sacc[0][0];
 #pragma unroll
@@ -235,7 +248,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][i]);
         mx = pair_max(mx);
         const float m_tile = mx * c;
-        const bool grow = m_tile > m_ref + tau;     // always true on the first tile (m_ref = -inf)
+        // always true on the first tile (m_ref = -inf); false for a row with every key of the tile masked
+        const bool grow = m_tile > m_ref + tau;
         if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // wavefront-uniform: rescale only when some row needs it
             const float m_new = grow ? m_tile : m_ref;
             const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exactly 1 for rows that keep m_ref
@@ -249,8 +263,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p,
     // left in pb as MFMA B-operands
-    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto tail_tag) {
-        constexpr bool TAIL = decltype(tail_tag)::value;
+    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) {
+        constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
         float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -258,8 +272,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[nb][i], c, -m_ref));
-                if constexpr (TAIL) {
-                    if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) >= S) p = 0.f;
+                if constexpr (MASK) {
+                    if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) > klim) p = 0.f;
                 }
                 psum[i & 3] += p;
                 pb[nb][i >> 3][i & 7] = (T)p;
@@ -299,39 +313,41 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     scores(KSLOT0, s_a);
     __syncthreads();   // step 0 overwrites K slot 0: every wavefront must have read it first
 
-    // step with tile j's scores in `cur`: PAR = j & 1 selects the slots
-    auto step = [&](int j, f32x16 (&cur)[NB], f32x16 (&nxt)[NB], auto par_tag) {
+    // step with tile j's scores in `cur`: PAR = j & 1 selects the slots, MASK the masked code path
+    auto step = [&](int j, f32x16 (&cur)[NB], f32x16 (&nxt)[NB], auto par_tag, auto mask_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         load_tile(k_rsrc, k_goff, j + 2, lds + (PAR ? KSLOT1 : KSLOT0));
         load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
-        row_max(cur, j, std::false_type{});
+        row_max(cur, j, mask_tag);
         scores(PAR ? KSLOT0 : KSLOT1, nxt);
-        exponentials(cur, j, pb, std::false_type{});
+        exponentials(cur, j, pb, mask_tag);
         accumulate(PAR ? VSLOT1 : VSLOT0, pb);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
-    auto last = [&](f32x16 (&cur)[NB], int vslot) {
-        if (nT * TN != S) {
-            row_max(cur, nT - 1, std::true_type{});
-            exponentials(cur, nT - 1, pb, std::true_type{});
-        } else {
-            row_max(cur, nT - 1, std::false_type{});
-            exponentials(cur, nT - 1, pb, std::false_type{});
-        }
+    auto last = [&](int j, f32x16 (&cur)[NB], int vslot) {
+        row_max(cur, j, std::true_type{});
+        exponentials(cur, j, pb, std::true_type{});
         accumulate(vslot, pb);
     };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    // tiles 0 .. nfull-1 need no mask: they run in pairs through the unmasked step; the few tiles
+    // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
+    // masked path, which is also correct for a tile that turns out to need no mask
+    const int nsteps = nTw - 1;                               // steps that have a next tile
+    const int fast_end = (nsteps < nfull ? nsteps : nfull) & ~1;
     int j = 0;
-    for (; j + 2 < nT; j += 2) {
-        step(j, s_a, s_b, std::integral_constant<int, 0>{});
-        step(j + 1, s_b, s_a, std::integral_constant<int, 1>{});
+    for (; j < fast_end; j += 2) {
+        step(j, s_a, s_b, P0{}, std::false_type{});
+        step(j + 1, s_b, s_a, P1{}, std::false_type{});
     }
-    if (j + 1 < nT) {          // two tiles left: j (even) then j+1 (odd, last)
-        step(j, s_a, s_b, std::integral_constant<int, 0>{});
-        last(s_b, VSLOT1);
-    } else {                   // one tile left: j (even, last)
-        last(s_a, VSLOT0);
+    for (; j < nsteps; ++j) {
+        if (j & 1) step(j, s_b, s_a, P1{}, std::true_type{});
+        else       step(j, s_a, s_b, P0{}, std::true_type{});
     }
+    if (j & 1) last(j, s_b, VSLOT1);
+    else       last(j, s_a, VSLOT0);
 
     // ---- O_i = o_i / l_i (Section 4.1.2), rounded once to the 16-bit output type.  The accumulators
     // hold O^T (a lane owns one query row and scattered groups of 4 columns), so the tile is turned

@@ -14,6 +14,7 @@ struct LaunchArgs {
     float tau;        // lazy-rescale threshold in log2 units (0 = raise the reference on every new maximum)
     uint32_t qsign;   // 0x80008000 when scale < 0 (sign folded into Q), else 0
     int linear_grid;
+    int causal;       // causal mask (Section 4.1.3): key j contributes to query i only if j <= i
     hipStream_t stream;
 };
 

@@ -101,6 +101,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
     a.linear_grid = (flags & TSDPA_FLAG_LINEAR_GRID) ? 1 : 0;
+    a.causal = (flags & TSDPA_FLAG_CAUSAL) ? 1 : 0;
     a.stream = (hipStream_t)stream;
 
     int err;

@@ -115,7 +115,7 @@ def test_python_front_end_rejects_host_tensors_and_causal():
     x = torch.zeros(1, 1, 4, 64, dtype=torch.float16)
     with pytest.raises(ValueError):
         binding.sdpa(x, x, x)
-    with pytest.raises(NotImplementedError):
+    with pytest.raises(ValueError):
         binding.sdpa(x, x, x, causal=True)
 
 

@@ -36,20 +36,21 @@ def _device():
     torch.cuda.synchronize()
 
 
-def gpu_sdpa(q, k, v, scale=None, tile=None, flags=0, return_lse=True):
+def gpu_sdpa(q, k, v, scale=None, tile=None, flags=0, return_lse=True, causal=False):
     qd, kd, vd = (t.cuda() for t in (q, k, v))
-    o, lse = binding.sdpa(qd, kd, vd, scale=scale, return_lse=True, tile=tile, flags=flags)
+    o, lse = binding.sdpa(qd, kd, vd, causal=causal, scale=scale, return_lse=True, tile=tile, flags=flags)
     torch.cuda.synchronize()
     return o.cpu(), lse.cpu()
 
 
-def check(q, k, v, dtype, scale=None, tile=None, rows=None, flags=0, tag=""):
-    say(f"[case] {tag} shape={tuple(q.shape)} dtype={dtype} scale={scale} tile={tile} rows={'all' if rows is None else len(rows)}")
-    o, lse = gpu_sdpa(q, k, v, scale=scale, tile=tile, flags=flags)
+def check(q, k, v, dtype, scale=None, tile=None, rows=None, flags=0, tag="", causal=False):
+    say(f"[case] {tag} shape={tuple(q.shape)} dtype={dtype} scale={scale} tile={tile} causal={causal} "
+        f"rows={'all' if rows is None else len(rows)}")
+    o, lse = gpu_sdpa(q, k, v, scale=scale, tile=tile, flags=flags, causal=causal)
     assert torch.isfinite(o.float()).all(), "non-finite output"
     assert torch.isfinite(lse).all(), "non-finite lse"
     ref_o, ref_lse = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy(),
-                              scale=scale, rows=rows, return_lse=True)
+                              scale=scale, rows=rows, return_lse=True, causal=causal)
     got_o = o.double().numpy()
     got_lse = lse.double().numpy()
     if rows is not None:
@@ -188,6 +189,43 @@ def test_mfma_probe_runs_and_reports_its_flops():
     binding.probe_mfma(binding.BF16, False, 1, sink.data_ptr(), stream)
     torch.cuda.synchronize()
     assert float(sink[0]) == 64 * 16 * 16      # 64 MFMAs x 16 accumulator elements summed x 16
+
+
+# ------------------------------------------------------------------ causal mask (Section 4.1.3)
+@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("dtype,D", [("f16", 64), ("bf16", 128), ("bf16", 64), ("f16", 128)])
+def test_causal_small_shapes_all_tiles(dtype, D, tile):
+    for S in (1, 2, 31, 33, 64, 65, 127, 128, 129, 197, 256, 300, 513):
+        q, k, v = make_qkv(2, 2, S, D, dtype, seed=9000 + S)
+        check(q, k, v, dtype, tile=tile, causal=True, tag=f"causal S={S}")
+
+
+def test_causal_scale_variants_and_first_row():
+    q, k, v = make_qkv(1, 2, 260, 64, "f16", seed=91)
+    for scale in (0.0, -0.3, 1.0):
+        check(q, k, v, "f16", scale=scale, causal=True, tag=f"causal scale={scale}")
+    o, _ = gpu_sdpa(q, k, v, causal=True)
+    assert torch.equal(o[:, :, 0], v[:, :, 0])          # row 0 sees key 0 only
+
+
+def test_causal_rows_do_not_depend_on_later_keys_or_values():
+    q, k, v = make_qkv(1, 2, 700, 128, "bf16", seed=92)
+    o1, l1 = gpu_sdpa(q, k, v, causal=True)
+    k2, v2 = k.clone(), v.clone()
+    k2[:, :, 400:] = 7.0
+    v2[:, :, 400:] = -9.0
+    o2, l2 = gpu_sdpa(q, k2, v2, causal=True)
+    assert torch.equal(o1[:, :, :400], o2[:, :, :400]) and torch.equal(l1[:, :, :400], l2[:, :, :400])
+    assert not torch.equal(o1[:, :, 400:], o2[:, :, 400:])
+
+
+def test_causal_text_regime_full_and_long_context_sampled():
+    w, q, k, v = make_workload("C2", "bf16")
+    check(q, k, v, "bf16", causal=True, tag="C2 causal")
+    w, q, k, v = make_workload("C4")
+    rows = sample_rows(w.S, limit=40)
+    check(q, k, v, "bf16", causal=True, rows=rows, tag="C4 causal, sampled rows")
+    check(q, k, v, "bf16", causal=True, rows=rows, tile=(64, 128), tag="C4 causal, sampled rows")
 
 
 # ------------------------------------------------------------------ the five configurations
