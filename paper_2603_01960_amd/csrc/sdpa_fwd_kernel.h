@@ -178,8 +178,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         v_goff[it] = r * G::ROW + ((cp ^ (G::vswz(r) << 2)) << 4);
     }
     auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) {
-        // wavefront-uniform offset; rows >= S fall outside the descriptor and read as zeros without a
-        // memory access, and so does a tile this workgroup does not need (index moved past the end)
+        // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
+        // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
+        // outside the descriptor and read as zeros without a memory access, and so does a tile this
+        // workgroup does not need (its index is moved past the end)
         const int soff = (j < nTw ? j : nT) * G::TILE;
 #pragma unroll
         for (int it = 0; it < NLD; ++it)

@@ -145,6 +145,30 @@ def test_no_write_outside_the_output_and_no_read_dependence_past_S():
     assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["bf16"]
 
 
+@pytest.mark.parametrize("S,D,tile", [(197, 64, (128, 32)), (197, 64, (64, 128)), (130, 128, (128, 64)),
+                                      (64, 128, (64, 32)), (256, 64, (128, 64)), (33, 128, (128, 128))])
+@pytest.mark.parametrize("causal", [False, True])
+def test_nothing_is_read_past_the_end_of_k_and_v(S, D, tile, causal):
+    """K and V end exactly where a NaN-filled region starts.  A row index >= S of the LAST head that
+    was fetched from memory (ragged tail, or a tile prefetched past the end) would bring NaN into the
+    V operand, and 0 * NaN = NaN would reach the output."""
+    B, H = 1, 2
+    q, k, v = make_qkv(B, H, S, D, "bf16", seed=55)
+    n = B * H * S * D
+    guard = 1 << 17
+    bufs = []
+    for t in (k, v):
+        buf = torch.full((n + guard,), float("nan"), dtype=torch.bfloat16, device="cuda")
+        buf[:n] = t.flatten().cuda()
+        bufs.append(buf)
+    kd, vd = (b[:n].view(B, H, S, D) for b in bufs)
+    o, lse = binding.sdpa(q.cuda(), kd, vd, causal=causal, return_lse=True, tile=tile)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+    ref = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy(), causal=causal)
+    assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["bf16"]
+
+
 def test_non_default_stream_and_repeatability():
     q, k, v = make_qkv(2, 4, 777, 128, "f16", seed=61)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
