@@ -48,6 +48,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: B2 H32 S8192 D128 BF16)")
     ap.add_argument("--dtype", default=None, help="f16 / bf16 (default: the workload's first dtype)")
+    ap.add_argument("--shape", default=None, help="B,H,S,D: a custom shape (seeded N(0,1) inputs) instead of --workload")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
@@ -66,9 +67,15 @@ def parse_args():
     return ap.parse_args()
 
 
-def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal"):
-    from paper_2603_01960_amd.workloads import make_workload
-    w, q, k, v = make_workload(name, dtype)
+def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal", shape=None):
+    from paper_2603_01960_amd.workloads import Workload, make_qkv, make_workload
+    if shape is not None:
+        B, H, S, D = shape
+        dtype = dtype or "bf16"
+        w = Workload(f"custom", B, H, S, D, (dtype,), 4242)
+        q, k, v = make_qkv(B, H, S, D, dtype, w.seed)
+    else:
+        w, q, k, v = make_workload(name, dtype)
     dtype = dtype or w.dtypes[0]
     if fill != "normal":
         q, k, v = (torch.zeros_like(t) if fill == "zeros" else torch.ones_like(t) for t in (q, k, v))
@@ -205,7 +212,8 @@ def main():
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0) \
         | (pkg.binding.FLAG_CAUSAL if args.causal else 0)
 
-    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill)
+    shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape)
     w, dtype = r["workload"], r["dtype"]
     flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
     tflops = flops / (r["ms_per_step"] * 1e-3) / 1e12
@@ -222,7 +230,7 @@ def main():
         gbs = comp_bytes / (r["kernel_ms_avg"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4)}
-    roofline["traffic"] = None if args.causal else MEASURED_TRAFFIC_BYTES.get((w.name, dtype))
+    roofline["traffic"] = None if args.causal or args.input_fill != "normal" else MEASURED_TRAFFIC_BYTES.get((w.name, dtype))
     roofline["kernel"] = f"sdpa_fwd_kernel<{dtype},D={w.D},T_M={tm},T_N={tn}>"
     roofline["kernel_ms_avg"] = round(r["kernel_ms_avg"], 5)
     roofline["kernel_ms_median"] = round(r["kernel_ms_median"], 5)

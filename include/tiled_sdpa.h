@@ -32,11 +32,12 @@ enum { TSDPA_F16 = 0, TSDPA_BF16 = 1 };
 enum {
     TSDPA_OK = 0,
     TSDPA_ERR_NULL_PTR = 1,      /* q, k, v or o is NULL while B*H*S > 0                    */
-    TSDPA_ERR_BAD_SHAPE = 2,     /* negative B, H or S; B*H*ceil(S/64) or (S+1024)*D*2 overflows int */
+    TSDPA_ERR_BAD_SHAPE = 2,     /* negative B, H or S; B*H*ceil(S/64) overflows int; (S+1024)*D*2 >= 2^30 */
     TSDPA_ERR_BAD_DTYPE = 3,     /* dtype is neither TSDPA_F16 nor TSDPA_BF16               */
-    TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64 or 128                                      */
+    TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64, 96, 128 or 160                             */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
-    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}          */
+    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}, or
+                                    tile_n = 128 at D = 160 (does not fit the LDS)          */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8         /* the HIP runtime refused the launch                      */
 };
@@ -63,7 +64,7 @@ enum {
  *             normaliser of row i, which is what merging partial results over key ranges needs.
  *   S       : any length >= 0; key columns beyond S contribute nothing and rows beyond S are
  *             neither computed into memory nor read past the tensor end.
- *   D       : 64 or 128.
+ *   D       : 64, 96, 128 or 160 (the head dims of the paper's grid, Section 4.3).
  *   scale   : multiplies Q K^T; any finite value.  NaN selects the default 1/sqrt(D)
  *             (Section 4.2.1), since C has no default arguments.
  *   stream  : hipStream_t (NULL = default stream).  The call returns once the kernel is enqueued.

@@ -1,0 +1,6 @@
+// Forward-kernel instantiations: element type bf16, head dim 96.
+#include "sdpa_fwd_inst.h"
+
+namespace tsdpa {
+int launch_bf16_d96(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<__bf16, 96>(tile_m, tile_n, a); }
+}  // namespace tsdpa

@@ -1,0 +1,6 @@
+// Forward-kernel instantiations: element type f16, head dim 160.
+#include "sdpa_fwd_inst.h"
+
+namespace tsdpa {
+int launch_f16_d160(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<_Float16, 160>(tile_m, tile_n, a); }
+}  // namespace tsdpa

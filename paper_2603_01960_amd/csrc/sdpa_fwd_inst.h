@@ -45,10 +45,14 @@ int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a)
     switch (key) {
         case 64032: return launch_one<T, D, 2, 32>(a);
         case 64064: return launch_one<T, D, 2, 64>(a);
-        case 64128: return launch_one<T, D, 2, 128>(a);
+        case 64128:
+            if constexpr (TileGeom<D, 128>::LDS_BYTES <= kLdsPerCU) return launch_one<T, D, 2, 128>(a);
+            else return (int)hipErrorInvalidValue;   // D = 160: four 128-row tiles exceed the LDS
         case 128032: return launch_one<T, D, 4, 32>(a);
         case 128064: return launch_one<T, D, 4, 64>(a);
-        case 128128: return launch_one<T, D, 4, 128>(a);
+        case 128128:
+            if constexpr (TileGeom<D, 128>::LDS_BYTES <= kLdsPerCU) return launch_one<T, D, 4, 128>(a);
+            else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }
 }

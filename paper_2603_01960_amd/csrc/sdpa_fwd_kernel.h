@@ -89,12 +89,18 @@ __device__ __forceinline__ float pair_sum(float x) {
 //      same chunk of 16 consecutive rows; the swizzle spreads them over all 64 banks.
 //   V: 64-byte block b of row r sits at b ^ vswz(r).  The transposing read has 32 lanes fetch one
 //      64-byte block of 4 consecutive rows; the swizzle puts those on 4 x 16 distinct banks.
+// Head dims that are not a power of two (96, 160) use the LDS geometry of the next power of two
+// (DG = 128, 256): rows are DG*2 bytes apart and the chunks past D are never fetched (the lanes that
+// would fill them aim outside the buffer descriptor and receive zeros without a memory access).
 template <int D, int TN> struct TileGeom {
-    static constexpr int ROW = D * 2;            // bytes per row
-    static constexpr int TILE = TN * ROW;        // bytes per K or V tile
-    static constexpr int LDS_BYTES = 4 * TILE;   // K slots 0,1 then V slots 0,1
-    static __host__ __device__ constexpr int kswz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-    static __host__ __device__ constexpr int vswz(int r) { return D == 128 ? (r & 3) : ((r >> 1) & 1); }
+    static constexpr int DG = D <= 64 ? 64 : (D <= 128 ? 128 : 256);
+    static constexpr int ROW = DG * 2;              // bytes per LDS row
+    static constexpr int GROW = D * 2;              // bytes per row in global memory
+    static constexpr int TILE = TN * ROW;           // bytes per K or V tile in LDS
+    static constexpr int GTILE = TN * GROW;         // ... and in global memory
+    static constexpr int LDS_BYTES = 4 * TILE;      // K slots 0,1 then V slots 0,1
+    static __host__ __device__ constexpr int kswz(int r) { return DG == 64 ? ((r >> 1) & 7) : (r & 15); }
+    static __host__ __device__ constexpr int vswz(int r) { return DG == 64 ? ((r >> 1) & 1) : (r & 3); }
 };
 
 // Workgroup -> (head, query tile).  Hardware deals consecutive workgroup ids round-robin over the
@@ -122,7 +128,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using vec4 = typename E::vec4;
     using G = TileGeom<D, TN>;
     constexpr int TM = NW * 32;
-    constexpr int CPR = D / 8;                    // 16-byte chunks per row
+    constexpr int CPR = G::DG / 8;                // 16-byte chunks per LDS row
+    constexpr int GCPR = D / 8;                   // ... of which this many hold data
     constexpr int NLD = TN * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
     static_assert(NLD >= 1 && (TN * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
     constexpr int NB = TN / 32, KK = D / 16, DB = D / 32;
@@ -167,22 +174,24 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // so a row index >= S reads as zeros instead of touching memory.  Load instruction `it` of this
     // wavefront fills LDS chunks [(it*NW + wave)*64, +64) of the tile; lane `lane` fills chunk p of
     // that range and therefore fetches the global chunk that the swizzle maps to position p.
-    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + head_off), (short)0, S * G::ROW, 0x00020000);
-    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + head_off), (short)0, S * G::ROW, 0x00020000);
+    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + head_off), (short)0, S * G::GROW, 0x00020000);
+    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + head_off), (short)0, S * G::GROW, 0x00020000);
+    constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
     int k_goff[NLD], v_goff[NLD];
 #pragma unroll
     for (int it = 0; it < NLD; ++it) {
         const int p = (it * NW + wave) * 64 + lane;
         const int r = p / CPR, cp = p % CPR;
-        k_goff[it] = r * G::ROW + ((cp ^ G::kswz(r)) << 4);
-        v_goff[it] = r * G::ROW + ((cp ^ (G::vswz(r) << 2)) << 4);
+        const int kc = cp ^ G::kswz(r), vc = cp ^ (G::vswz(r) << 2);   // global chunk that belongs at LDS chunk cp
+        k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
+        v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
     }
     auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) {
         // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
         // outside the descriptor and read as zeros without a memory access, and so does a tile this
         // workgroup does not need (its index is moved past the end)
-        const int soff = (j < nTw ? j : nT) * G::TILE;
+        const int soff = (j < nTw ? j : nT) * G::GTILE;
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
@@ -372,7 +381,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 vec4 out;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) out[e] = (T)(oacc[db][q4 * 4 + e] * inv);
-                const int chunk = db * 4 + q4;        // columns chunk*8 .. +7; this lane owns half g of it
+                const int chunk = db * 4 + q4;        // columns chunk*8 .. +7 (< D); this lane owns half g of it
                 *(TSDPA_LDS vec4 *)(ow + l32 * G::ROW + ((chunk ^ (l32 & CMASK)) << 4) + g * 8) = out;
             }
         // the region is private to this wavefront: LDS operations of one wavefront complete in order
@@ -382,7 +391,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         for (int i = 0; i < 32 / RPI; ++i) {
             const int r = i * RPI + lane / CPR, cc = lane % CPR;
             const u32x4 val = lds_read128(ow + r * G::ROW + ((cc ^ (r & CMASK)) << 4));
-            if (qrow0 + r < S)
+            if (qrow0 + r < S && cc < GCPR)
                 *(u32x4 *)(o + head_off + (size_t)(qrow0 + r) * D + cc * 8) = val;
         }
     }

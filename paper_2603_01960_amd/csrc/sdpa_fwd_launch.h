@@ -20,8 +20,12 @@ struct LaunchArgs {
 
 // Each returns a hipError_t cast to int (0 = success); tile_m in {64,128}, tile_n in {32,64,128}.
 int launch_f16_d64(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_f16_d96(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_f16_d128(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_f16_d160(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_bf16_d64(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_bf16_d96(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_bf16_d128(int tile_m, int tile_n, const LaunchArgs &a);
+int launch_bf16_d160(int tile_m, int tile_n, const LaunchArgs &a);
 
 }  // namespace tsdpa

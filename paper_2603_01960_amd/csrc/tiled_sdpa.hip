@@ -12,32 +12,37 @@ namespace {
 
 constexpr int kVersion = 100;  // 0.1.0
 
-bool valid_tile(int tm, int tn) { return (tm == 64 || tm == 128) && (tn == 32 || tn == 64 || tn == 128); }
+bool valid_tile(int tm, int tn, int D)
+{
+    if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64 || tn == 128)) return false;
+    return !(D == 160 && tn == 128);   // four 128 x 512-byte tiles do not fit the 160 KB LDS
+}
 
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
 void pick_tile(int BH, int S, int D, int *tm, int *tn)
 {
     (void)BH;
-    (void)D;
-    // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts, two workgroups per
+        // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts, two workgroups per
     // CU) wins at every configuration measured; 64-row K/V tiles for long sequences, 32-row tiles when
     // there are only a few tiles per head, so the pipeline fills sooner and the ragged tail wastes less.
     *tm = 128;
     *tn = S >= 512 ? 64 : 32;
+    if (D == 160) *tn = 32;       // 512-byte LDS rows: keeps two workgroups per CU
     if (S <= 64) *tm = 64;
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
 {
     if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
-    if (D != 64 && D != 128) return TSDPA_ERR_UNSUPPORTED_D;
+    if (D != 64 && D != 96 && D != 128 && D != 160) return TSDPA_ERR_UNSUPPORTED_D;
     if (B < 0 || H < 0 || S < 0) return TSDPA_ERR_BAD_SHAPE;
     const int64_t bh = (int64_t)B * (int64_t)H;
     // the grid is B*H*ceil(S/tile_m) <= B*H*ceil(S/64) workgroups and must fit an int
     if (bh > 0 && S > 0 && bh * (((int64_t)S + 63) / 64) > (int64_t)std::numeric_limits<int>::max())
         return TSDPA_ERR_BAD_SHAPE;
-    // one head's K (or V) is addressed through a 32-bit byte range, prefetch distance included
-    if (((int64_t)S + 1024) * D * 2 > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
+    // one head's K (or V) is addressed through a 32-bit byte range with room for a "fetch nothing"
+    // offset above it: keep it, prefetch distance included, below 2^30 bytes
+    if (((int64_t)S + 1024) * D * 2 >= ((int64_t)1 << 30)) return TSDPA_ERR_BAD_SHAPE;
     return TSDPA_OK;
 }
 
@@ -54,7 +59,7 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_NULL_PTR: return "null pointer for q, k, v or o";
         case TSDPA_ERR_BAD_SHAPE: return "bad shape: B, H, S must be >= 0 and the grid must fit an int";
         case TSDPA_ERR_BAD_DTYPE: return "bad dtype: expected TSDPA_F16 or TSDPA_BF16";
-        case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64 or 128";
+        case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64, 96, 128 or 160";
         case TSDPA_ERR_MISALIGNED: return "misaligned pointer: q, k, v, o need 16-byte, lse 4-byte alignment";
         case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128}, or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
@@ -84,7 +89,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     if (tile_m == 0 && tile_n == 0)
         pick_tile(B * H, S, D, &tile_m, &tile_n);
-    else if (!valid_tile(tile_m, tile_n))
+    else if (!valid_tile(tile_m, tile_n, D))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
     if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
@@ -105,10 +110,21 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     a.stream = (hipStream_t)stream;
 
     int err;
-    if (dtype == TSDPA_F16)
-        err = (D == 64) ? tsdpa::launch_f16_d64(tile_m, tile_n, a) : tsdpa::launch_f16_d128(tile_m, tile_n, a);
-    else
-        err = (D == 64) ? tsdpa::launch_bf16_d64(tile_m, tile_n, a) : tsdpa::launch_bf16_d128(tile_m, tile_n, a);
+    if (dtype == TSDPA_F16) {
+        switch (D) {
+            case 64: err = tsdpa::launch_f16_d64(tile_m, tile_n, a); break;
+            case 96: err = tsdpa::launch_f16_d96(tile_m, tile_n, a); break;
+            case 128: err = tsdpa::launch_f16_d128(tile_m, tile_n, a); break;
+            default: err = tsdpa::launch_f16_d160(tile_m, tile_n, a); break;
+        }
+    } else {
+        switch (D) {
+            case 64: err = tsdpa::launch_bf16_d64(tile_m, tile_n, a); break;
+            case 96: err = tsdpa::launch_bf16_d96(tile_m, tile_n, a); break;
+            case 128: err = tsdpa::launch_bf16_d128(tile_m, tile_n, a); break;
+            default: err = tsdpa::launch_bf16_d160(tile_m, tile_n, a); break;
+        }
+    }
     return err == 0 ? TSDPA_OK : TSDPA_ERR_LAUNCH;
 }
 

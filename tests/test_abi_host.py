@@ -53,7 +53,8 @@ P = 0x1000  # fake, aligned, never dereferenced: every case below fails validati
 @pytest.mark.parametrize("kwargs,expect", [
     (dict(dtype=2), DTYPE),
     (dict(dtype=-1), DTYPE),
-    (dict(D=96), BAD_D),
+    (dict(D=80), BAD_D),
+    (dict(D=192), BAD_D),
     (dict(D=0), BAD_D),
     (dict(B=-1), SHAPE),
     (dict(S=-5), SHAPE),
@@ -71,6 +72,9 @@ P = 0x1000  # fake, aligned, never dereferenced: every case below fails validati
     (dict(tile_m=32, tile_n=64), TILE),
     (dict(tile_m=128, tile_n=0), TILE),
     (dict(tile_m=128, tile_n=256), TILE),
+    (dict(D=160, tile_m=128, tile_n=128), TILE),
+    (dict(D=160, tile_m=64, tile_n=64, S=0), OK),
+    (dict(S=1 << 23, D=128), SHAPE),
     (dict(scale=math.inf), SCALE),
     (dict(scale=-math.inf), SCALE),
 ])
@@ -87,6 +91,7 @@ def test_validation_order_and_codes(lib, kwargs, expect):
 def test_plain_entry_point_validates_too(lib):
     assert binding.tiled_sdpa_fwd(None, P, P, P, None, 1, 1, 16, 64, 0.125, 0, None) == NULL
     assert binding.tiled_sdpa_fwd(P, P, P, P, None, 1, 1, 16, 80, 0.125, 0, None) == BAD_D
+    assert binding.tiled_sdpa_fwd(None, P, P, P, None, 1, 1, 16, 96, 0.125, 0, None) == NULL
     assert binding.tiled_sdpa_fwd(None, None, None, None, None, 0, 4, 16, 64, 0.125, 1, None) == OK
 
 
@@ -103,9 +108,9 @@ def test_probe_validates_before_touching_the_gpu(lib):
 
 def test_default_tile_is_a_legal_tile(lib):
     for S in (1, 32, 64, 197, 1024, 16384):
-        for D in (64, 128):
+        for D in (64, 96, 128, 160):
             tm, tn = binding.default_tile(2, 4, S, D, binding.BF16)
-            assert tm in (64, 128) and tn in (32, 64, 128)
+            assert tm in (64, 128) and tn in (32, 64, 128) and not (D == 160 and tn == 128)
     with pytest.raises(binding.TiledSdpaError):
         binding.default_tile(1, 1, 16, 72, 0)
 

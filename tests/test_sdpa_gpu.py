@@ -146,7 +146,8 @@ def test_no_write_outside_the_output_and_no_read_dependence_past_S():
 
 
 @pytest.mark.parametrize("S,D,tile", [(197, 64, (128, 32)), (197, 64, (64, 128)), (130, 128, (128, 64)),
-                                      (64, 128, (64, 32)), (256, 64, (128, 64)), (33, 128, (128, 128))])
+                                      (64, 128, (64, 32)), (256, 64, (128, 64)), (33, 128, (128, 128)),
+                                      (197, 96, (128, 64)), (130, 160, (128, 32)), (70, 160, (64, 64))])
 @pytest.mark.parametrize("causal", [False, True])
 def test_nothing_is_read_past_the_end_of_k_and_v(S, D, tile, causal):
     """K and V end exactly where a NaN-filled region starts.  A row index >= S of the LAST head that
@@ -213,6 +214,40 @@ def test_mfma_probe_runs_and_reports_its_flops():
     binding.probe_mfma(binding.BF16, False, 1, sink.data_ptr(), stream)
     torch.cuda.synchronize()
     assert float(sink[0]) == 64 * 16 * 16      # 64 MFMAs x 16 accumulator elements summed x 16
+
+
+# ------------------------------------------------------------------ head dims 96 and 160 (Section 4.3 grid)
+@pytest.mark.parametrize("tile", TILES)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("D", [96, 160])
+@pytest.mark.parametrize("causal", [False, True])
+def test_head_dims_96_and_160(D, dtype, tile, causal):
+    if D == 160 and tile[1] == 128:
+        q, k, v = make_qkv(1, 1, 64, D, dtype, seed=1)
+        with pytest.raises(binding.TiledSdpaError):
+            binding.sdpa(q.cuda(), k.cuda(), v.cuda(), tile=tile)
+        return
+    for S in (1, 33, 64, 127, 197, 256, 300, 513):
+        q, k, v = make_qkv(2, 2, S, D, dtype, seed=9500 + S + D)
+        check(q, k, v, dtype, tile=tile, causal=causal, tag=f"D={D} S={S}")
+
+
+@pytest.mark.parametrize("D", [96, 160])
+def test_head_dims_96_and_160_mid_size_default_tile_and_guards(D):
+    q, k, v = make_qkv(2, 4, 1024, D, "bf16", seed=9600 + D)
+    check(q, k, v, "bf16", tag=f"D={D} S=1024")
+    check(q, k, v, "bf16", causal=True, tag=f"D={D} S=1024 causal")
+    # output rows are D wide in memory: nothing may be written between or after them
+    B, H, S = 1, 2, 197
+    q, k, v = make_qkv(B, H, S, D, "f16", seed=9700 + D)
+    n, pad = B * H * S * D, 4096
+    buf = torch.full((n + 2 * pad,), 7.0, dtype=torch.float16, device="cuda")
+    o = buf[pad:pad + n].view(B, H, S, D)
+    binding.sdpa(q.cuda(), k.cuda(), v.cuda(), out=o)
+    torch.cuda.synchronize()
+    assert (buf[:pad] == 7.0).all() and (buf[pad + n:] == 7.0).all()
+    ref = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy())
+    assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["f16"]
 
 
 # ------------------------------------------------------------------ causal mask (Section 4.1.3)
