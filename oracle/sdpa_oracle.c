@@ -30,6 +30,15 @@
  * (nullable), p [BH, nrows, S] double (nullable; the softmax probabilities
  * e_ij / L_i, zero for masked keys, exposed for the rows-sum-to-one pin).
  *
+ * sdpa_oracle_rows_kv is the same definition with Sq query rows against Skv
+ * key/value rows (the KV-cache / decoding shapes of the paper's roadmap,
+ * Section 8): q is [BH, Sq, D], k and v are [BH, Skv, D], and Eq. 1's score
+ * matrix is Sq x Skv.  The paper defines the causal mask only for Sq = Skv;
+ * the reading taken here is that the Sq queries are the LAST Sq positions of
+ * the Skv-long sequence, so query row i sits at position i + (Skv - Sq) and
+ * sees keys j <= i + (Skv - Sq).  Causal with Skv < Sq is rejected (its first
+ * rows would see no key at all).
+ *
  * Returns 0, or a negative number for bad arguments / allocation failure.
  */
 #include <math.h>
@@ -47,18 +56,21 @@ int sdpa_oracle_num_threads(void)
 #endif
 }
 
-int sdpa_oracle_rows(const float *q, const float *k, const float *v,
-                     long BH, long S, long D, double scale,
-                     const long *rows, long nrows, int causal,
-                     double *o, double *lse, double *p)
+int sdpa_oracle_rows_kv(const float *q, const float *k, const float *v,
+                        long BH, long Sq, long Skv, long D, double scale,
+                        const long *rows, long nrows, int causal,
+                        double *o, double *lse, double *p)
 {
     if (!q || !k || !v || !o) return -1;
-    if (BH < 0 || S < 0 || D <= 0) return -2;
-    if (!rows) nrows = S;
+    if (BH < 0 || Sq < 0 || Skv < 0 || D <= 0) return -2;
+    if (causal && Skv < Sq) return -2;
+    if (!rows) nrows = Sq;
     if (nrows < 0) return -2;
-    if (BH == 0 || S == 0 || nrows == 0) return 0;
+    if (BH == 0 || Sq == 0 || nrows == 0) return 0;
+    if (Skv == 0) return -2;                 /* a softmax over no keys is undefined */
     for (long r = 0; rows && r < nrows; ++r)
-        if (rows[r] < 0 || rows[r] >= S) return -3;
+        if (rows[r] < 0 || rows[r] >= Sq) return -3;
+    const long S = Skv;                      /* length of a score row */
 
     int failed = 0;
     const long total = BH * nrows;
@@ -76,12 +88,13 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
             const long bh = t / nrows;
             const long r = t % nrows;
             const long i = rows ? rows[r] : r;
-            const float *qi = q + (bh * S + i) * D;
-            const float *kb = k + bh * S * D;
-            const float *vb = v + bh * S * D;
+            const float *qi = q + (bh * Sq + i) * D;
+            const float *kb = k + bh * Skv * D;
+            const float *vb = v + bh * Skv * D;
 
-            /* scores and their maximum; masked keys (j > i under the causal mask) are left out */
-            const long J = causal ? i + 1 : S;
+            /* scores and their maximum; masked keys (after the query's position under the causal
+               mask) are left out */
+            const long J = causal ? i + (Skv - Sq) + 1 : Skv;
             double M = -INFINITY;
             for (long j = 0; j < J; ++j) {
                 const float *kj = kb + j * D;
@@ -112,4 +125,12 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
         free(acc);
     }
     return failed ? -4 : 0;
+}
+
+int sdpa_oracle_rows(const float *q, const float *k, const float *v,
+                     long BH, long S, long D, double scale,
+                     const long *rows, long nrows, int causal,
+                     double *o, double *lse, double *p)
+{
+    return sdpa_oracle_rows_kv(q, k, v, BH, S, S, D, scale, rows, nrows, causal, o, lse, p);
 }

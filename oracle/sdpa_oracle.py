@@ -50,10 +50,10 @@ def _load():
     if _lib is None:
         build()
         lib = ctypes.CDLL(str(_LIB))
-        lib.sdpa_oracle_rows.restype = ctypes.c_int
-        lib.sdpa_oracle_rows.argtypes = [
+        lib.sdpa_oracle_rows_kv.restype = ctypes.c_int
+        lib.sdpa_oracle_rows_kv.argtypes = [
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
-            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_long, ctypes.c_int,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.sdpa_oracle_num_threads.restype = ctypes.c_int
@@ -80,23 +80,28 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False, causa
     """Materialised float64 attention, Eq. 1 (Section 3.1) with M = 0, or with the causal mask of
     Section 4.1.3 (keys after the query are left out) when ``causal`` is set.
 
-    q, k, v: arrays of shape [..., S, D] (leading dims are batch/head and must
-    agree).  scale: defaults to 1/sqrt(D) (Section 4.2.1); if given it is used
+    q: [..., Sq, D]; k, v: [..., Skv, D] (leading dims are batch/head and must
+    agree; Sq = Skv = S is the paper's case, Sq != Skv the KV-cache / decoding
+    shapes of its roadmap, Section 8, where under ``causal`` the queries are the
+    last Sq positions of the Skv-long sequence: row i sees keys j <= i + Skv - Sq).
+    scale: defaults to 1/sqrt(D) (Section 4.2.1); if given it is used
     as the float32 value the device receives, promoted to double.
     rows: optional 1-D sequence of query-row indices evaluated for every
     batch/head.  Returns o [..., nrows, D] float64 (and lse [..., nrows],
-    p [..., nrows, S] on request).
+    p [..., nrows, Skv] on request).
     """
     q32, k32, v32 = _as_f32(q), _as_f32(k), _as_f32(v)
-    if q32.shape != k32.shape or q32.shape != v32.shape or q32.ndim < 2:
-        raise ValueError("q, k, v must have identical shape [..., S, D]")
-    lead, (S, D) = q32.shape[:-2], q32.shape[-2:]
+    if (k32.shape != v32.shape or q32.ndim < 2 or q32.ndim != k32.ndim
+            or q32.shape[:-2] != k32.shape[:-2] or q32.shape[-1] != k32.shape[-1]):
+        raise ValueError("q must be [..., Sq, D] and k, v [..., Skv, D] with equal leading dims and D")
+    lead, (Sq, D) = q32.shape[:-2], q32.shape[-2:]
+    S = k32.shape[-2]
     BH = int(np.prod(lead, dtype=np.int64)) if lead else 1
     if scale is None:
         scale = 1.0 / np.sqrt(np.float64(D))
     scale = float(np.float32(scale))
     if rows is None:
-        rows_arr, nrows, rows_ptr = None, S, None
+        rows_arr, nrows, rows_ptr = None, Sq, None
     else:
         rows_arr = np.ascontiguousarray(rows, dtype=np.int64)
         if rows_arr.ndim != 1:
@@ -105,13 +110,13 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False, causa
     o = np.empty((BH, nrows, D), dtype=np.float64)
     lse = np.empty((BH, nrows), dtype=np.float64) if return_lse else None
     p = np.empty((BH, nrows, S), dtype=np.float64) if return_p else None
-    rc = _load().sdpa_oracle_rows(
-        q32.ctypes.data, k32.ctypes.data, v32.ctypes.data, BH, S, D, scale,
+    rc = _load().sdpa_oracle_rows_kv(
+        q32.ctypes.data, k32.ctypes.data, v32.ctypes.data, BH, Sq, S, D, scale,
         rows_ptr, nrows, 1 if causal else 0, o.ctypes.data,
         lse.ctypes.data if lse is not None else None,
         p.ctypes.data if p is not None else None)
     if rc != 0:
-        raise RuntimeError(f"sdpa_oracle_rows failed with status {rc}")
+        raise RuntimeError(f"sdpa_oracle_rows_kv failed with status {rc}")
     out = [o.reshape(*lead, nrows, D)]
     if return_lse:
         out.append(lse.reshape(*lead, nrows))
@@ -122,7 +127,8 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False, causa
 
 def sdpa_numpy(q, k, v, scale=None, return_lse=False, causal=False):
     """Eq. 1 (Section 3.1) as numpy float64 matrix expressions; M = 0, or the causal mask
-    (M_ij = -inf for j > i, Section 4.1.3) added to the scaled scores exactly as Eq. 1 writes it."""
+    (M_ij = -inf for j > i, Section 4.1.3) added to the scaled scores exactly as Eq. 1 writes it.
+    With Sq query rows against Skv >= Sq keys the mask is M_ij = -inf for j > i + Skv - Sq."""
     q64 = np.asarray(q, dtype=np.float64)
     k64 = np.asarray(k, dtype=np.float64)
     v64 = np.asarray(v, dtype=np.float64)
@@ -132,8 +138,10 @@ def sdpa_numpy(q, k, v, scale=None, return_lse=False, causal=False):
     scale = float(np.float32(scale))
     s = scale * (q64 @ np.swapaxes(k64, -1, -2))
     if causal:
-        S = s.shape[-1]
-        s = s + np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, 0.0)
+        Sq, S = s.shape[-2:]
+        if S < Sq:
+            raise ValueError("causal needs Skv >= Sq")
+        s = s + np.where(np.arange(S)[None, :] > np.arange(Sq)[:, None] + (S - Sq), -np.inf, 0.0)
     m = s.max(axis=-1, keepdims=True)
     e = np.exp(s - m)
     L = e.sum(axis=-1, keepdims=True)
@@ -146,31 +154,32 @@ def sdpa_numpy(q, k, v, scale=None, return_lse=False, causal=False):
 def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False, causal=False):
     """Blockwise online-softmax attention, Section 4.1.2 (Eqs. 2-4), in float64.
 
-    One [S, D] problem.  ``tile_bounds`` is an increasing list of key indices
-    0 = b_0 < b_1 < ... < b_T = S; tile t holds keys b_t .. b_{t+1}-1.  For each
+    One problem: q [Sq, D] against k, v [S, D] (Sq = S in the paper).  ``tile_bounds`` is an
+    increasing list of key indices 0 = b_0 < b_1 < ... < b_T = S; tile t holds keys b_t .. b_{t+1}-1.  For each
     tile, in the paper's order: scores, running max (Eq. 2), normaliser (Eq. 3),
     output accumulator (Eq. 4); after the last tile O_i = o_i / l_i.  The state
     starts at m = -inf, l = 0, o = 0 (the paper does not state the start; any
     start with l = 0, o = 0 and m below every score gives the same result).
-    With ``causal`` the scores of keys after the query are set to -inf before the
-    update (a row whose keys in a tile are all masked keeps its state).
+    With ``causal`` the scores of keys after the query (j > i + S - Sq) are set to -inf before
+    the update (a row whose keys in a tile are all masked keeps its state).
     """
     q64 = np.asarray(q, dtype=np.float64)
     k64 = np.asarray(k, dtype=np.float64)
     v64 = np.asarray(v, dtype=np.float64)
-    S, D = q64.shape
+    Sq, D = q64.shape
+    S = k64.shape[0]
     if scale is None:
         scale = 1.0 / np.sqrt(np.float64(D))
     scale = float(np.float32(scale))
     if tile_bounds is None:
         tile_bounds = [0, S]
-    m = np.full(S, -np.inf)
-    l = np.zeros(S)
-    o = np.zeros((S, D))
+    m = np.full(Sq, -np.inf)
+    l = np.zeros(Sq)
+    o = np.zeros((Sq, D))
     for lo, hi in zip(tile_bounds[:-1], tile_bounds[1:]):
         s_tile = scale * (q64 @ k64[lo:hi].T)                    # S_ij for this tile
         if causal:                                               # mask, then update (Section 4.1.2)
-            s_tile = np.where(np.arange(lo, hi)[None, :] > np.arange(S)[:, None], -np.inf, s_tile)
+            s_tile = np.where(np.arange(lo, hi)[None, :] > np.arange(Sq)[:, None] + (S - Sq), -np.inf, s_tile)
         m_old = m
         m = np.maximum(m_old, s_tile.max(axis=1))                # Eq. 2
         with np.errstate(invalid="ignore"):

@@ -451,3 +451,98 @@ def test_causal_pins_catch_planted_mask_mistakes():
     assert fails(lambda i, j: (j < i) | (i == 0))               # diagonal off by one (too narrow)
     assert fails(lambda i, j: j >= i)                           # mask transposed
     assert fails(lambda i, j: j == j)                           # no mask
+
+
+# ------------------------------------------- Sq query rows against Skv keys (decoding shapes, Section 8)
+def _brute_force_kv(q, k, v, scale, causal):
+    """Rational dot products and 50-digit exponentials for q [Sq, D] against k, v [Skv, D]; under the
+    causal mask the queries are the last Sq positions of the sequence."""
+    getcontext().prec = 50
+    (Sq, D), Skv = q.shape, k.shape[0]
+    sc = Fraction(float(scale))
+    out, lses = [], []
+    for i in range(Sq):
+        pos = i + (Skv - Sq)                          # position of query i in the Skv-long sequence
+        keys = [j for j in range(Skv) if not causal or j <= pos]
+        w = []
+        for j in keys:
+            x = sc * sum(Fraction(float(q[i, d])) * Fraction(float(k[j, d])) for d in range(D))
+            w.append((Decimal(x.numerator) / Decimal(x.denominator)).exp())
+        tot = sum(w)
+        out.append([float(sum(wj * Decimal(float(v[j, d])) for wj, j in zip(w, keys)) / tot) for d in range(D)])
+        lses.append(float(tot.ln()))
+    return np.array(out), np.array(lses)
+
+
+@pytest.mark.parametrize("Sq,Skv,D", [(1, 1, 2), (1, 9, 4), (3, 7, 4), (4, 5, 3), (6, 6, 2), (7, 3, 2)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_kv_shapes_brute_force_tiny(Sq, Skv, D, causal):
+    if causal and Skv < Sq:
+        pytest.skip("causal needs Skv >= Sq")
+    q = _rand((Sq, D), 600 + Sq, std=1.5)
+    k, v = _rand((Skv, D), 601 + Skv, std=1.5), _rand((Skv, D), 602 + Skv, std=1.5)
+    scale = float(np.float32(1 / math.sqrt(D)))
+    ref_o, ref_lse = _brute_force_kv(q, k, v, scale, causal)
+    for fn in (orc.sdpa, orc.sdpa_numpy):
+        o, lse = fn(q, k, v, return_lse=True, causal=causal)
+        assert o.shape == (Sq, D) and lse.shape == (Sq,)
+        np.testing.assert_allclose(o, ref_o, atol=1e-12, rtol=0)
+        np.testing.assert_allclose(lse, ref_lse, atol=1e-12, rtol=0)
+    o, lse = orc.sdpa_online(q, k, v, return_lse=True, causal=causal, tile_bounds=sorted({0, (Skv + 1) // 2, Skv}))
+    np.testing.assert_allclose(o, ref_o, atol=1e-12, rtol=0)
+    np.testing.assert_allclose(lse, ref_lse, atol=1e-12, rtol=0)
+
+
+@pytest.mark.parametrize("Sq,Skv", [(1, 300), (17, 130), (64, 64), (100, 257)])
+def test_kv_shapes_against_torch_float64(Sq, Skv):
+    q = _rand((2, 2, Sq, 64), 610, std=1.3)
+    k, v = _rand((2, 2, Skv, 64), 611, std=1.3), _rand((2, 2, Skv, 64), 612, std=1.3)
+    tq, tk, tv = (torch.from_numpy(x.astype(np.float64)) for x in (q, k, v))
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, scale=0.125).numpy()
+    np.testing.assert_allclose(orc.sdpa(q, k, v), ref, atol=1e-12, rtol=0)
+    # causal: an explicit boolean mask with the queries as the last Sq positions
+    keep = torch.ones(Sq, Skv, dtype=torch.bool).tril(diagonal=Skv - Sq)
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=keep, scale=0.125).numpy()
+    o, lse = orc.sdpa(q, k, v, causal=True, return_lse=True)
+    np.testing.assert_allclose(o, ref, atol=1e-12, rtol=0)
+    s = 0.125 * (tq @ tk.transpose(-1, -2)).masked_fill(~keep, -math.inf)
+    np.testing.assert_allclose(lse, torch.logsumexp(s, -1).numpy(), atol=1e-12, rtol=0)
+    rows = sorted({0, Sq // 2, Sq - 1})
+    assert np.array_equal(orc.sdpa(q, k, v, causal=True, rows=rows), o[..., rows, :])
+
+
+def test_decode_step_is_the_last_row_of_the_square_causal_problem():
+    """One new query against a cache of Skv keys = the last row of causal self-attention over Skv
+    positions; a chunk of queries a..b-1 against keys 0..b-1 = rows a..b-1 of the square problem."""
+    q, k, v = (_rand((3, 90, 32), 620 + i, std=1.4) for i in range(3))
+    tq, tk, tv = (torch.from_numpy(x.astype(np.float64)) for x in (q, k, v))
+    scale = float(np.float32(32 ** -0.5))
+    sq = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, is_causal=True, scale=scale).numpy()
+    np.testing.assert_allclose(orc.sdpa(q[:, -1:], k, v, causal=True), sq[:, -1:], atol=1e-12, rtol=0)
+    np.testing.assert_allclose(orc.sdpa(q[:, -1:], k, v, causal=False), sq[:, -1:], atol=1e-12, rtol=0)
+    a, b = 40, 77
+    np.testing.assert_allclose(orc.sdpa(q[:, a:b], k[:, :b], v[:, :b], causal=True), sq[:, a:b], atol=1e-12, rtol=0)
+
+
+def test_kv_shapes_closed_forms_and_planted_offset_mistakes():
+    # zero queries: row i is the mean of the value rows it may see (all Skv, or the first i+Skv-Sq+1)
+    k, v = _rand((23, 8), 630), _rand((23, 8), 631).astype(np.float64)
+    q0 = np.zeros((5, 8), np.float16)
+    o, lse = orc.sdpa(q0, k, v.astype(np.float32), return_lse=True)
+    np.testing.assert_allclose(o, np.broadcast_to(v.mean(0), (5, 8)), atol=1e-13)
+    np.testing.assert_allclose(lse, math.log(23), atol=1e-13)
+    o, lse = orc.sdpa(q0, k, v.astype(np.float32), return_lse=True, causal=True)
+    for i in range(5):
+        n = i + 23 - 5 + 1
+        np.testing.assert_allclose(o[i], v[:n].mean(0), atol=1e-13)
+        np.testing.assert_allclose(lse[i], math.log(n), atol=1e-13)
+
+    # the same closed form rejects plausible wrong alignments of the mask
+    def mean_rows(offset):
+        return np.stack([v[:max(1, min(23, i + offset + 1))].mean(0) for i in range(5)])
+    assert np.allclose(o, mean_rows(23 - 5), atol=1e-13)
+    assert not np.allclose(o, mean_rows(0), atol=1e-6)              # top-left alignment
+    assert not np.allclose(o, mean_rows(23 - 5 - 1), atol=1e-6)     # one position short
+    assert not np.allclose(o, mean_rows(23 - 5 + 1), atol=1e-6)     # one position long
+    with pytest.raises(RuntimeError):
+        orc.sdpa(np.zeros((6, 8), np.float16), k[:5], v[:5].astype(np.float32), causal=True)   # Skv < Sq
