@@ -49,6 +49,9 @@ def parse_args():
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: B2 H32 S8192 D128 BF16)")
     ap.add_argument("--dtype", default=None, help="f16 / bf16 (default: the workload's first dtype)")
     ap.add_argument("--shape", default=None, help="B,H,S,D: a custom shape (seeded N(0,1) inputs) instead of --workload")
+    ap.add_argument("--kv", default=None,
+                    help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
+    ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
@@ -166,6 +169,58 @@ def copy_calibration(torch, mib, steps):
                       "GBs_read_plus_write": round(2 * n / ms / 1e6, 1)}), flush=True)
 
 
+def bench_kv(pkg, torch, args, tile, flags):
+    """One JSON line for tiled_sdpa_fwd_kv on a seeded B,H,Sq,Skv,D problem (both of its kernels timed
+    as one step; output and workspace are allocated once, outside the timed region)."""
+    from paper_2603_01960_amd.workloads import make_qkv
+    B, H, Sq, Skv, D = (int(x) for x in args.kv.split(","))
+    dtype = args.dtype or "bf16"
+    code = pkg.F16 if dtype == "f16" else pkg.BF16
+    q = make_qkv(B, H, Sq, D, dtype, seed=4242)[0].cuda()
+    _, k, v = (t.cuda() for t in make_qkv(B, H, Skv, D, dtype, seed=4243))
+    splits = args.splits or pkg.kv_default_splits(B, H, Sq, Skv, D, code, flags)
+    ws = torch.empty(max(16, pkg.kv_workspace_bytes(B, H, Sq, D, splits)), dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q)
+    run = lambda: pkg.sdpa_kv(q, k, v, splits=splits, out=o, workspace=ws, tile=tile, flags=flags)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    a.record()
+    for _ in range(args.steps):
+        run()
+    b.record()
+    torch.cuda.synchronize()
+    wall_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms = a.elapsed_time(b) / args.steps
+    assert torch.isfinite(o.float()).all().item(), "non-finite output"
+    causal = bool(flags & pkg.binding.FLAG_CAUSAL)
+    pairs = Sq * Skv - (Sq * (Sq - 1) // 2 if causal else 0)        # (query, key) pairs that contribute
+    flops = 4.0 * B * H * pairs * D
+    comp_bytes = 2.0 * B * H * D * (2 * Skv + 2 * Sq)
+    ridge = PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if flops / comp_bytes >= ridge:
+        tf = flops / (ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(tf / PEAK_MFMA_TFLOPS, 4)}
+    else:
+        gbs = comp_bytes / (ms * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    roofline.update({"traffic": None, "kernel": "sdpa_fwd_kernel<KV> + sdpa_merge_kernel" if splits > 1 else "sdpa_fwd_kernel<KV>",
+                     "ms_avg_both_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
+                     "compulsory_hbm_bytes_per_launch": comp_bytes})
+    print(json.dumps({
+        "metric": "SDPA forward TFLOP/s (4*B*H*pairs*D / t)", "value": round(flops / (wall_ms * 1e-3) / 1e12, 3),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"KV: SDPA fwd {'causal' if causal else 'non-causal'} B={B} H={H} Sq={Sq} Skv={Skv} D={D} {dtype}",
+                   "splits": splits, "tile": list(tile) if tile else "heuristic",
+                   "cache_tokens_per_s": round(B * H * Skv / (ms * 1e-3), 1)},
+        "roofline": roofline}), flush=True)
+
+
 def cpu_baseline(w, q, k, v, target_seconds):
     """Time the unmodified float64 CPU checker on a bounded sample of the same workload."""
     from oracle import sdpa_oracle
@@ -212,6 +267,9 @@ def main():
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0) \
         | (pkg.binding.FLAG_CAUSAL if args.causal else 0)
 
+    if args.kv:
+        bench_kv(pkg, torch, args, tile, flags)
+        return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape)
     w, dtype = r["workload"], r["dtype"]

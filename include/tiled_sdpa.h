@@ -39,8 +39,13 @@ enum {
     TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}, or
                                     tile_n = 128 at D = 160 (does not fit the LDS)          */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
-    TSDPA_ERR_LAUNCH = 8         /* the HIP runtime refused the launch                      */
+    TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
+    TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split: workspace NULL, not 16-byte
+                                    aligned, or smaller than tiled_sdpa_kv_workspace_bytes reports */
+    TSDPA_ERR_BAD_SPLITS = 10    /* splits < 0 or > TSDPA_MAX_SPLITS                         */
 };
+
+enum { TSDPA_MAX_SPLITS = 128 };
 
 /* flags for tiled_sdpa_fwd_ex */
 enum {
@@ -87,6 +92,45 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
 
 /* The (tile_m, tile_n) the heuristic picks for a shape; returns a status code. */
 int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, int *tile_m, int *tile_n);
+
+/*
+ * Forward pass for Sq query rows against Skv key/value rows, with the key range optionally split
+ * over several workgroups: the KV-cache / decoding shapes that the paper names as future work
+ * (Section 8), and the cure for shapes whose B*H*ceil(Sq/tile_m) workgroups cannot fill the GPU.
+ * Each split runs the recurrence of Section 4.1.2 (Eqs. 2-4) over its own contiguous run of K/V
+ * tiles and leaves its state (o, m, l) in the workspace; a second kernel combines the states with
+ * the rescaling of Eqs. 3-4 and applies the final O_i = o_i / l_i.
+ *
+ *   q        : [B, H, Sq, D];  k, v : [B, H, Skv, D];  o : [B, H, Sq, D];  lse : NULL or FP32 [B, H, Sq].
+ *              Layout, alignment, D, scale, dtype, stream as for tiled_sdpa_fwd.
+ *   flags    : TSDPA_FLAG_CAUSAL takes the Sq queries to be the LAST Sq positions of the Skv-long
+ *              sequence (the paper defines the mask for Sq = Skv only): key j contributes to query
+ *              row i only if j <= i + Skv - Sq.  It needs Skv >= Sq.  The other flags as above.
+ *   tile_m   : 64 or 128;  tile_n : 32 or 64;  both 0 = heuristic.
+ *   splits   : workgroups per (head, query tile) along the key axis, 1..TSDPA_MAX_SPLITS; 0 = the
+ *              value tiled_sdpa_kv_default_splits reports for this shape and these flags.
+ *   workspace: device memory for the split states, 16-byte aligned, at least
+ *              tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, n) bytes, n being `splits` or, for splits = 0,
+ *              the heuristic's value; ignored (may be NULL) when n = 1, where O is written directly.
+ *              Owned by the caller; the library uses it only between the two kernels of this call, so
+ *              calls that may overlap on the GPU need distinct workspaces.  Its contents afterwards
+ *              are unspecified.  More splits than there are K/V tiles are allowed (the surplus ones
+ *              contribute nothing) but waste workspace.
+ *
+ * Skv = 0 with Sq > 0 is TSDPA_ERR_BAD_SHAPE (a softmax over no keys).  Validation order: dtype, D,
+ * shape, empty problem (B*H*Sq == 0), null pointers, alignment, tile, scale, splits, workspace, launch.
+ */
+int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, float *lse,
+                      int B, int H, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                      int tile_m, int tile_n, unsigned flags,
+                      int splits, void *workspace, unsigned long long workspace_bytes);
+
+/* Splits the heuristic picks (1 when the query tiles alone fill the GPU); returns a status code. */
+int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags, int *splits);
+
+/* Workspace bytes tiled_sdpa_fwd_kv needs for `splits` >= 1 (a value from tiled_sdpa_kv_default_splits,
+ * or the caller's own): B*H*splits*Sq*(D+2) floats.  0 for splits <= 1 or negative arguments. */
+unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, int splits);
 
 /*
  * Measurement aid, not part of the attention path: enqueue a register-resident stream of

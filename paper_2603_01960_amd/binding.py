@@ -23,6 +23,9 @@ EXPORTS = (
     "tiled_sdpa_fwd",
     "tiled_sdpa_fwd_ex",
     "tiled_sdpa_default_tile",
+    "tiled_sdpa_fwd_kv",
+    "tiled_sdpa_kv_default_splits",
+    "tiled_sdpa_kv_workspace_bytes",
     "tiled_sdpa_probe_mfma",
     "tiled_sdpa_status_string",
     "tiled_sdpa_version",
@@ -56,6 +59,13 @@ def load_library():
     lib.tiled_sdpa_fwd_ex.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint]
     lib.tiled_sdpa_default_tile.restype = ci
     lib.tiled_sdpa_default_tile.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.tiled_sdpa_fwd_kv.restype = ci
+    lib.tiled_sdpa_fwd_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint,
+                                      ci, vp, ctypes.c_ulonglong]
+    lib.tiled_sdpa_kv_default_splits.restype = ci
+    lib.tiled_sdpa_kv_default_splits.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.c_uint, ctypes.POINTER(ci)]
+    lib.tiled_sdpa_kv_workspace_bytes.restype = ctypes.c_ulonglong
+    lib.tiled_sdpa_kv_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.tiled_sdpa_probe_mfma.restype = ci
     lib.tiled_sdpa_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tiled_sdpa_status_string.restype = ctypes.c_char_p
@@ -82,6 +92,18 @@ def default_tile(B: int, H: int, S: int, D: int, dtype: int):
     return tm.value, tn.value
 
 
+def kv_default_splits(B: int, H: int, Sq: int, Skv: int, D: int, dtype: int, flags: int = 0) -> int:
+    n = ctypes.c_int(0)
+    st = load_library().tiled_sdpa_kv_default_splits(B, H, Sq, Skv, D, dtype, flags, ctypes.byref(n))
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return n.value
+
+
+def kv_workspace_bytes(B: int, H: int, Sq: int, D: int, splits: int) -> int:
+    return int(load_library().tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits))
+
+
 def probe_mfma(dtype: int, random_operands: bool, iters: int, sink=None, stream=None) -> float:
     """Enqueue the MFMA-only stream (see tiled_sdpa_probe_mfma); returns its flop count.
 
@@ -104,6 +126,61 @@ def tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dt
                       tile_m=0, tile_n=0, flags=0) -> int:
     return int(load_library().tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D,
                                                 float(scale), dtype, stream, tile_m, tile_n, flags))
+
+
+def tiled_sdpa_fwd_kv(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Sq, Skv, D, scale, dtype, stream,
+                      tile_m=0, tile_n=0, flags=0, splits=0, workspace_ptr=None, workspace_bytes=0) -> int:
+    return int(load_library().tiled_sdpa_fwd_kv(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Sq, Skv, D,
+                                                float(scale), dtype, stream, tile_m, tile_n, flags,
+                                                splits, workspace_ptr, workspace_bytes))
+
+
+def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, return_lse: bool = False,
+            out=None, workspace=None, tile=None, flags: int = 0):
+    """Attention of q [B, H, Sq, D] over k, v [B, H, Skv, D] (KV-cache / decoding shapes), the key range
+    split over ``splits`` workgroups per query tile (0 = heuristic).  Under ``causal`` the queries are
+    the last Sq positions of the sequence.  ``workspace`` (any contiguous device tensor of enough bytes)
+    is allocated through torch when not given and needed.
+    """
+    import torch
+
+    if causal:
+        flags |= FLAG_CAUSAL
+    for name, t in (("q", q), ("k", k), ("v", v)):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise ValueError(f"{name} must be a device tensor")
+        if t.dim() != 4 or not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [B, H, S, D]")
+    if q.dtype not in (torch.float16, torch.bfloat16) or k.dtype != q.dtype or v.dtype != q.dtype:
+        raise ValueError("q, k, v must share dtype float16 or bfloat16")
+    if k.shape != v.shape or q.shape[:2] != k.shape[:2] or q.shape[3] != k.shape[3]:
+        raise ValueError("q must be [B, H, Sq, D] and k, v [B, H, Skv, D]")
+    if k.device != q.device or v.device != q.device:
+        raise ValueError("q, k, v must be on one device")
+    B, H, Sq, D = q.shape
+    Skv = k.shape[2]
+    dtype = F16 if q.dtype == torch.float16 else BF16
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
+        raise ValueError("out must match q in shape, dtype, device and be contiguous")
+    lse = torch.empty((B, H, Sq), dtype=torch.float32, device=q.device) if return_lse else None
+    tm, tn = tile if tile is not None else (0, 0)
+    n = splits if splits else kv_default_splits(B, H, Sq, Skv, D, dtype, flags)
+    need = kv_workspace_bytes(B, H, Sq, D, n)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        st = tiled_sdpa_fwd_kv(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                               lse.data_ptr() if lse is not None else None,
+                               B, H, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
+                               tm, tn, flags, n, ws_ptr, ws_bytes)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return (out, lse) if return_lse else out
 
 
 def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False, out=None,

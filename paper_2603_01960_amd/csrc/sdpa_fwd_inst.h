@@ -1,5 +1,6 @@
 // Instantiates the forward kernel for one (element type, head dim) over the tile grid
-// T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs) and provides its launcher.
+// T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs), plus the general Sq x Skv / split-KV
+// variant over T_M in {64,128} x T_N in {32,64}, and provides its launcher.
 // The kernel table is fixed at build time: there is no JIT step to cache (Section 4.2.2).
 #pragma once
 #include <mutex>
@@ -17,11 +18,11 @@ template <int D, int NW, int TN> constexpr int waves_per_simd() {
     return w < 1 ? 1 : (w > 2 ? 2 : w);
 }
 
-template <typename T, int D, int NW, int TN>
+template <typename T, int D, int NW, int TN, bool KV = false>
 int launch_one(const LaunchArgs &a)
 {
     constexpr int WPS = waves_per_simd<D, NW, TN>();
-    auto kern = sdpa_fwd_kernel<T, D, NW, TN, WPS>;
+    auto kern = sdpa_fwd_kernel<T, D, NW, TN, WPS, KV>;
     constexpr int lds_bytes = TileGeom<D, TN>::LDS_BYTES;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -31,10 +32,11 @@ int launch_one(const LaunchArgs &a)
     if (attr_err != hipSuccess) return (int)attr_err;
     constexpr int TM = NW * 32;
     const int nQ = (a.S + TM - 1) / TM;
-    const int N = a.BH * nQ;
+    const int N = a.BH * nQ * (KV ? a.splits : 1);
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
-                       a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal);
+                       a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal,
+                       a.Skv, a.splits, a.ws);
     return (int)hipGetLastError();
 }
 
@@ -42,6 +44,15 @@ template <typename T, int D>
 int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a)
 {
     const int key = tile_m * 1000 + tile_n;
+    if (a.kv) {
+        switch (key) {
+            case 64032: return launch_one<T, D, 2, 32, true>(a);
+            case 64064: return launch_one<T, D, 2, 64, true>(a);
+            case 128032: return launch_one<T, D, 4, 32, true>(a);
+            case 128064: return launch_one<T, D, 4, 64, true>(a);
+            default: return (int)hipErrorInvalidValue;
+        }
+    }
     switch (key) {
         case 64032: return launch_one<T, D, 2, 32>(a);
         case 64064: return launch_one<T, D, 2, 64>(a);

@@ -37,6 +37,7 @@ typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef short i16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define TSDPA_LDS __attribute__((address_space(3)))
 typedef TSDPA_LDS unsigned char *lds_ptr;
@@ -116,11 +117,19 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
 // s_waitcnt vmcnt(0) with the other counters left at their maxima (gfx9 encoding)
 #define TSDPA_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
-template <typename T, int D, int NW, int TN, int WPS>
+// KV = false is the paper's problem: S query rows against the same S key rows, one workgroup per
+// (head, query tile), final output.  KV = true generalises it for the decoding shapes of the paper's
+// roadmap (Section 8): S query rows against Skv key rows (under the causal mask the queries are the
+// last S positions of the sequence), and the key range of every (head, query tile) cut into `splits`
+// contiguous runs of tiles, one workgroup each.  With splits > 1 a workgroup writes its unnormalised
+// state (o, m, l of Eqs. 2-4) to `ws` instead of O: o as float [BH][splits][S][D], followed by
+// (m, l) pairs as float [BH][splits][S][2]; sdpa_merge_kernel combines them.
+template <typename T, int D, int NW, int TN, int WPS, bool KV>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
-                float tau, uint32_t qsign, int linear_grid, int causal)
+                float tau, uint32_t qsign, int linear_grid, int causal,
+                int Skv_arg, int splits_arg, float *__restrict__ ws)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     using E = Elem<T>;
@@ -141,11 +150,18 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
 
+    const int Skv = KV ? Skv_arg : S;             // key rows; S is the number of query rows
+    const int splits = KV ? splits_arg : 1;
+    const int koff = Skv - S;                     // position of query row 0 in the key sequence (causal)
     const int wg = remap_workgroup(blockIdx.x, N, linear_grid != 0);
-    const int head = wg / nQ;
+    // query tile fastest, then split, then head: neighbours share one run of K/V tiles
+    const int hs = wg / nQ;
+    const int head = KV ? hs / splits : hs;
+    const int sp = KV ? hs - head * splits : 0;
     // under the causal mask the work of a query tile grows with its index: start the long ones first
-    const int qt = causal ? nQ - 1 - (wg - head * nQ) : wg - head * nQ;
+    const int qt = causal ? nQ - 1 - (wg - hs * nQ) : wg - hs * nQ;
     const size_t head_off = (size_t)head * (size_t)S * D;
+    const size_t kv_off = (size_t)head * (size_t)Skv * D;
     const T *qh = q + head_off;
 
     // ---- Q rows of this wavefront as MFMA B-operands: lane holds Q[row l32][kk*16 + g*8 .. +7]
@@ -160,22 +176,26 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     // Tiles this workgroup streams, and how many leading ones need no mask for any of its rows.
-    // A key j contributes to query row i iff j <= klim(i): klim = S-1 (only the ragged tail is cut
-    // off), or min(i, S-1) under the causal mask of Section 4.1.3, where tiles strictly above the
-    // diagonal of the workgroup's last row are neither read nor computed.
-    const int nT = (S + TN - 1) / TN;
+    // A key j contributes to query row i iff j <= klim(i): klim = Skv-1 (only the ragged tail is cut
+    // off), or the query's own position min(i, S-1) + koff under the causal mask of Section 4.1.3,
+    // where tiles strictly above the diagonal of the workgroup's last row are neither read nor computed.
+    const int nT = (Skv + TN - 1) / TN;
     const int r0 = qt * TM;
     const int last_row = (r0 + TM < S ? r0 + TM : S) - 1;
-    const int nTw = causal ? last_row / TN + 1 : nT;
-    const int klim = causal ? (qrow < S ? qrow : S - 1) : S - 1;
-    const int nfull = ((causal ? (r0 < S - 1 ? r0 : S - 1) : S - 1) + 1) / TN;
+    const int nTw = causal ? (last_row + koff) / TN + 1 : nT;
+    const int klim = causal ? (qrow < S ? qrow : S - 1) + koff : Skv - 1;
+    const int nfull = ((causal ? (r0 < S - 1 ? r0 : S - 1) + koff : Skv - 1) + 1) / TN;
+    // this workgroup's run of tiles [t0, t1): all nTw of them unless the key range is split
+    const int per_split = (nTw + splits - 1) / splits;
+    const int t0 = KV ? sp * per_split : 0;
+    const int t1 = KV ? (t0 + per_split < nTw ? t0 + per_split : nTw) : nTw;
 
-    // ---- K/V tiles: HBM -> LDS.  One buffer descriptor per tensor covers exactly this head's S rows,
-    // so a row index >= S reads as zeros instead of touching memory.  Load instruction `it` of this
+    // ---- K/V tiles: HBM -> LDS.  One buffer descriptor per tensor covers exactly this head's Skv rows,
+    // so a row index >= Skv reads as zeros instead of touching memory.  Load instruction `it` of this
     // wavefront fills LDS chunks [(it*NW + wave)*64, +64) of the tile; lane `lane` fills chunk p of
     // that range and therefore fetches the global chunk that the swizzle maps to position p.
-    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + head_off), (short)0, S * G::GROW, 0x00020000);
-    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + head_off), (short)0, S * G::GROW, 0x00020000);
+    const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + kv_off), (short)0, Skv * G::GROW, 0x00020000);
+    const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
     int k_goff[NLD], v_goff[NLD];
 #pragma unroll
@@ -191,7 +211,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
         // outside the descriptor and read as zeros without a memory access, and so does a tile this
         // workgroup does not need (its index is moved past the end)
-        const int soff = (j < nTw ? j : nT) * G::GTILE;
+        const int soff = (j < t1 ? j : nT) * G::GTILE;
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
@@ -262,9 +282,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         // always true on the first tile (m_ref = -inf); false for a row with every key of the tile masked
         const bool grow = m_tile > m_ref + tau;
         if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // wavefront-uniform: rescale only when some row needs it
-            const float m_new = grow ? m_tile : m_ref;
-            const float alpha = __builtin_amdgcn_exp2f(m_ref - m_new);   // exactly 1 for rows that keep m_ref
-            m_ref = m_new;
+            // rows that keep m_ref are left alone (also one whose keys so far were all masked: m_ref = -inf)
+            const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_tile) : 1.0f;
+            m_ref = grow ? m_tile : m_ref;
             l_run *= alpha;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -316,15 +336,16 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // barrier that ended step j-1.
     f32x16 s_a[NB], s_b[NB];
     vec8 pb[NB][2];
-    load_tile(k_rsrc, k_goff, 0, lds + KSLOT0);
-    load_tile(v_rsrc, v_goff, 0, lds + VSLOT0);
-    load_tile(k_rsrc, k_goff, 1, lds + KSLOT1);   // past the end when nT == 1: zeros, never used
+    if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
+    load_tile(k_rsrc, k_goff, t0, lds + KSLOT0);
+    load_tile(v_rsrc, v_goff, t0, lds + VSLOT0);
+    load_tile(k_rsrc, k_goff, t0 + 1, lds + KSLOT1);   // past the end of a one-tile run: zeros, never used
     TSDPA_WAIT_VMCNT0();
     __syncthreads();
     scores(KSLOT0, s_a);
     __syncthreads();   // step 0 overwrites K slot 0: every wavefront must have read it first
 
-    // step with tile j's scores in `cur`: PAR = j & 1 selects the slots, MASK the masked code path
+    // step with tile j's scores in `cur`: PAR = (j - t0) & 1 selects the slots, MASK the masked code path
     auto step = [&](int j, f32x16 (&cur)[NB], f32x16 (&nxt)[NB], auto par_tag, auto mask_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         load_tile(k_rsrc, k_goff, j + 2, lds + (PAR ? KSLOT1 : KSLOT0));
@@ -343,22 +364,24 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
-    // tiles 0 .. nfull-1 need no mask: they run in pairs through the unmasked step; the few tiles
+    // tiles below nfull need no mask: they run in pairs through the unmasked step; the few tiles
     // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
     // masked path, which is also correct for a tile that turns out to need no mask
-    const int nsteps = nTw - 1;                               // steps that have a next tile
-    const int fast_end = (nsteps < nfull ? nsteps : nfull) & ~1;
-    int j = 0;
+    const int last_j = t1 - 1;                                // steps t0 .. last_j-1 have a next tile
+    const int fast_n = (last_j < nfull ? last_j : nfull) - t0;
+    const int fast_end = t0 + (fast_n > 0 ? fast_n & ~1 : 0);
+    int j = t0;
     for (; j < fast_end; j += 2) {
         step(j, s_a, s_b, P0{}, std::false_type{});
         step(j + 1, s_b, s_a, P1{}, std::false_type{});
     }
-    for (; j < nsteps; ++j) {
-        if (j & 1) step(j, s_b, s_a, P1{}, std::true_type{});
-        else       step(j, s_a, s_b, P0{}, std::true_type{});
+    for (; j < last_j; ++j) {
+        if ((j - t0) & 1) step(j, s_b, s_a, P1{}, std::true_type{});
+        else              step(j, s_a, s_b, P0{}, std::true_type{});
     }
-    if (j & 1) last(j, s_b, VSLOT1);
-    else       last(j, s_a, VSLOT0);
+    if ((j - t0) & 1) last(j, s_b, VSLOT1);
+    else              last(j, s_a, VSLOT0);
+    }
 
     // ---- O_i = o_i / l_i (Section 4.1.2), rounded once to the 16-bit output type.  The accumulators
     // hold O^T (a lane owns one query row and scattered groups of 4 columns), so the tile is turned
@@ -366,6 +389,29 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // XOR-swizzled by row against bank conflicts) and reads it back as whole rows, so that every global
     // store instruction writes complete, contiguous rows (16 B per lane) instead of 8-byte pieces.
     const float l_tot = pair_sum(l_run);
+    if (KV && splits > 1) {
+        // partial state of this split: the accumulators as they are (a lane owns query row qrow and
+        // groups of 4 consecutive columns), then the reference m and the normaliser l
+        const size_t prow = (size_t)(head * splits + sp) * S + qrow;
+        if (qrow < S) {
+            float *po = ws + prow * D;
+#pragma unroll
+            for (int db = 0; db < DB; ++db)
+#pragma unroll
+                for (int q4 = 0; q4 < 4; ++q4) {
+                    f32x4 part;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) part[e] = oacc[db][q4 * 4 + e];
+                    *(f32x4 *)(po + db * 32 + q4 * 8 + g * 4) = part;
+                }
+            if (g == 0) {
+                float *pml = ws + (size_t)(N / nQ) * S * D + prow * 2;   // N / nQ = BH * splits
+                pml[0] = m_ref;
+                pml[1] = l_tot;
+            }
+        }
+        return;
+    }
     const float inv = 1.0f / l_tot;
     if (lse != nullptr && g == 0 && qrow < S)
         lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;

@@ -1,0 +1,57 @@
+// Merge of split-KV partial states into the final output.
+//
+// Each split s of a query row holds the state of the online-softmax recurrence (Section 4.1.2,
+// Eqs. 2-4) after its own run of key tiles: a reference m_s (log2 units of the scaled scores), the
+// normaliser l_s and the unnormalised output o_s, both taken against m_s.  Because Eqs. 3-4 only ever
+// rescale by e^{m_old - m_new}, states over disjoint key ranges combine the same way:
+//     M = max_s m_s,   w_s = 2^(m_s - M),   L = sum_s w_s l_s,   O = (sum_s w_s o_s) / L,
+// and O_i = o_i / l_i as at the end of Section 4.1.2; LSE = (M + log2 L) ln 2.  A split that saw no
+// key of the row has (o, m, l) = (0, -inf, 0) and weight 0.
+//
+// Workspace layout (written by sdpa_fwd_kernel<..., KV = true>): o as float [BH][splits][S][D],
+// then (m, l) pairs as float [BH][splits][S][2].  One thread produces 4 consecutive output columns.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tsdpa {
+
+template <typename T>
+__global__ void __launch_bounds__(256)
+sdpa_merge_kernel(const float *__restrict__ ws, T *__restrict__ o, float *__restrict__ lse,
+                  int BH, int S, int D, int splits)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef T vec4 __attribute__((ext_vector_type(4)));
+    const int d4n = D / 4;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t rows = (size_t)BH * S;
+    if (idx >= rows * d4n) return;
+    const size_t r = idx / d4n;                   // bh * S + row
+    const int d4 = (int)(idx - r * d4n);
+    const size_t bh = r / S, row = r - bh * S;
+    const float *ml = ws + rows * splits * D;
+    const size_t first = (bh * splits) * S + row; // split s sits s*S rows further on
+
+    float M = -INFINITY;
+    for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[(first + (size_t)s * S) * 2]);
+    float L = 0.f;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int s = 0; s < splits; ++s) {
+        const size_t p = first + (size_t)s * S;
+        const float w = __builtin_amdgcn_exp2f(ml[p * 2] - M);   // 0 for a split with m = -inf (M is finite)
+        L += w * ml[p * 2 + 1];
+        const f32x4 part = *(const f32x4 *)(ws + p * D + d4 * 4);
+        acc += w * part;
+    }
+    const float inv = 1.0f / L;
+    vec4 out;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) out[e] = (T)(acc[e] * inv);
+    *(vec4 *)(o + r * D + d4 * 4) = out;
+    if (lse != nullptr && d4 == 0) lse[r] = (M + __builtin_amdgcn_logf(L)) * 0.69314718055994530942f;
+#endif
+}
+
+}  // namespace tsdpa

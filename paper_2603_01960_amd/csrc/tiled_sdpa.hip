@@ -7,10 +7,11 @@
 #include <limits>
 
 #include "sdpa_fwd_launch.h"
+#include "sdpa_merge_kernel.h"
 
 namespace {
 
-constexpr int kVersion = 100;  // 0.1.0
+constexpr int kVersion = 200;  // 0.2.0
 
 bool valid_tile(int tm, int tn, int D)
 {
@@ -46,6 +47,49 @@ int validate_shape(int B, int H, int S, int D, int dtype)
     return TSDPA_OK;
 }
 
+// Splits along the key axis (from timings on MI355X).  None when the query tiles alone give every CU
+// two workgroups.  Otherwise aim for two workgroups per CU if every split then still streams 32 tiles
+// or more (long caches: more loads in flight pay), else for one per CU, never cutting runs shorter
+// than 4 tiles for up to 64 query rows or 16 tiles beyond (each split of a query tile writes and the
+// merge re-reads T_M x D floats, which a short run does not amortise).
+int pick_splits(int BH, int Sq, int Skv, int tm, int tn)
+{
+    const int64_t base = (int64_t)BH * ((Sq + tm - 1) / tm);
+    const int64_t tiles = (Skv + tn - 1) / tn;
+    if (base <= 0 || base >= 512) return 1;
+    int64_t want = (512 + base - 1) / base;
+    if (tiles / want < 32) {
+        want = (256 + base - 1) / base;
+        const int64_t shortest = Sq <= 64 ? 4 : 16;
+        const int64_t most = tiles / shortest > 1 ? tiles / shortest : 1;
+        if (want > most) want = most;
+    }
+    if (want > TSDPA_MAX_SPLITS) want = TSDPA_MAX_SPLITS;
+    return (int)want;
+}
+
+int validate_shape_kv(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags)
+{
+    if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
+    if (D != 64 && D != 96 && D != 128 && D != 160) return TSDPA_ERR_UNSUPPORTED_D;
+    if (B < 0 || H < 0 || Sq < 0 || Skv < 0) return TSDPA_ERR_BAD_SHAPE;
+    const int64_t bh = (int64_t)B * (int64_t)H;
+    // B*H*ceil(Sq/64)*splits workgroups must fit an int
+    if (bh > 0 && Sq > 0 &&
+        bh * (((int64_t)Sq + 63) / 64) * TSDPA_MAX_SPLITS > (int64_t)std::numeric_limits<int>::max())
+        return TSDPA_ERR_BAD_SHAPE;
+    if (((int64_t)Skv + 1024) * D * 2 >= ((int64_t)1 << 30)) return TSDPA_ERR_BAD_SHAPE;
+    if (bh > 0 && Sq > 0 && Skv == 0) return TSDPA_ERR_BAD_SHAPE;
+    if ((flags & TSDPA_FLAG_CAUSAL) && Skv < Sq) return TSDPA_ERR_BAD_SHAPE;
+    return TSDPA_OK;
+}
+
+void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
+{
+    *tm = Sq <= 64 ? 64 : 128;
+    *tn = (Skv >= 512 && D != 160) ? 64 : 32;
+}
+
 }  // namespace
 
 extern "C" {
@@ -64,6 +108,8 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128}, or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
+        case TSDPA_ERR_WORKSPACE: return "split workspace is null, misaligned or too small";
+        case TSDPA_ERR_BAD_SPLITS: return "bad splits: must be 0 (heuristic) or 1..128";
         default: return "unknown status";
     }
 }
@@ -94,7 +140,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
     if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
 
-    tsdpa::LaunchArgs a;
+    tsdpa::LaunchArgs a{};
     a.q = q;
     a.k = k;
     a.v = v;
@@ -126,6 +172,98 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
         }
     }
     return err == 0 ? TSDPA_OK : TSDPA_ERR_LAUNCH;
+}
+
+unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, int splits)
+{
+    if (B < 0 || H < 0 || Sq < 0 || D < 0 || splits <= 1) return 0;
+    return (unsigned long long)B * H * splits * Sq * (D + 2) * sizeof(float);
+}
+
+int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags, int *splits)
+{
+    if (!splits) return TSDPA_ERR_NULL_PTR;
+    const int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
+    if (st != TSDPA_OK) return st;
+    int tm, tn;
+    pick_tile_kv(Sq, Skv, D, &tm, &tn);
+    *splits = pick_splits(B * H, Sq, Skv, tm, tn);
+    return TSDPA_OK;
+}
+
+int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, float *lse,
+                      int B, int H, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                      int tile_m, int tile_n, unsigned flags,
+                      int splits, void *workspace, unsigned long long workspace_bytes)
+{
+    int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
+    if (st != TSDPA_OK) return st;
+    if ((int64_t)B * H * Sq == 0) return TSDPA_OK;
+    if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
+    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o;
+    if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
+    if (tile_m == 0 && tile_n == 0)
+        pick_tile_kv(Sq, Skv, D, &tile_m, &tile_n);
+    else if (!(tile_m == 64 || tile_m == 128) || !(tile_n == 32 || tile_n == 64))
+        return TSDPA_ERR_BAD_TILE;
+    if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
+    if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
+    if (splits < 0 || splits > TSDPA_MAX_SPLITS) return TSDPA_ERR_BAD_SPLITS;
+    if (splits == 0) splits = pick_splits(B * H, Sq, Skv, tile_m, tile_n);
+    if (splits > 1) {
+        if (!workspace || ((uintptr_t)workspace & 15u) != 0 ||
+            workspace_bytes < tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits))
+            return TSDPA_ERR_WORKSPACE;
+    }
+
+    tsdpa::LaunchArgs a{};
+    a.q = q;
+    a.k = k;
+    a.v = v;
+    a.o = o;
+    a.lse = lse;
+    a.BH = B * H;
+    a.S = Sq;
+    a.c = std::fabs(scale) * 1.44269504088896340736f;
+    a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
+    a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
+    a.linear_grid = (flags & TSDPA_FLAG_LINEAR_GRID) ? 1 : 0;
+    a.causal = (flags & TSDPA_FLAG_CAUSAL) ? 1 : 0;
+    a.kv = 1;
+    a.Skv = Skv;
+    a.splits = splits;
+    a.ws = (float *)workspace;
+    a.stream = (hipStream_t)stream;
+
+    int err;
+    if (dtype == TSDPA_F16) {
+        switch (D) {
+            case 64: err = tsdpa::launch_f16_d64(tile_m, tile_n, a); break;
+            case 96: err = tsdpa::launch_f16_d96(tile_m, tile_n, a); break;
+            case 128: err = tsdpa::launch_f16_d128(tile_m, tile_n, a); break;
+            default: err = tsdpa::launch_f16_d160(tile_m, tile_n, a); break;
+        }
+    } else {
+        switch (D) {
+            case 64: err = tsdpa::launch_bf16_d64(tile_m, tile_n, a); break;
+            case 96: err = tsdpa::launch_bf16_d96(tile_m, tile_n, a); break;
+            case 128: err = tsdpa::launch_bf16_d128(tile_m, tile_n, a); break;
+            default: err = tsdpa::launch_bf16_d160(tile_m, tile_n, a); break;
+        }
+    }
+    if (err != 0) return TSDPA_ERR_LAUNCH;
+    if (splits > 1) {
+        const size_t threads = (size_t)B * H * Sq * (D / 4);
+        const unsigned blocks = (unsigned)((threads + 255) / 256);
+        if (dtype == TSDPA_F16)
+            hipLaunchKernelGGL(tsdpa::sdpa_merge_kernel<_Float16>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                               (const float *)workspace, (_Float16 *)o, lse, B * H, Sq, D, splits);
+        else
+            hipLaunchKernelGGL(tsdpa::sdpa_merge_kernel<__bf16>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
+                               (const float *)workspace, (__bf16 *)o, lse, B * H, Sq, D, splits);
+        if (hipGetLastError() != hipSuccess) return TSDPA_ERR_LAUNCH;
+    }
+    return TSDPA_OK;
 }
 
 int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,

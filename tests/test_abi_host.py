@@ -38,11 +38,11 @@ def test_library_exports_every_declared_symbol(lib):
 def test_version_and_status_strings(lib):
     assert binding.version() >= 100
     seen = set()
-    for code in range(0, 9):
+    for code in range(0, 11):
         s = binding.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 9
+    assert len(seen) == 11
     assert binding.status_string(12345) == "unknown status"
 
 
@@ -93,6 +93,58 @@ def test_plain_entry_point_validates_too(lib):
     assert binding.tiled_sdpa_fwd(P, P, P, P, None, 1, 1, 16, 80, 0.125, 0, None) == BAD_D
     assert binding.tiled_sdpa_fwd(None, P, P, P, None, 1, 1, 16, 96, 0.125, 0, None) == NULL
     assert binding.tiled_sdpa_fwd(None, None, None, None, None, 0, 4, 16, 64, 0.125, 1, None) == OK
+
+
+WORKSPACE, SPLITS = 9, 10
+
+
+@pytest.mark.parametrize("kwargs,expect", [
+    (dict(dtype=7), DTYPE),
+    (dict(D=72), BAD_D),
+    (dict(Sq=-1), SHAPE),
+    (dict(Skv=-1), SHAPE),
+    (dict(Skv=0), SHAPE),                          # a softmax over no keys
+    (dict(Skv=0, Sq=0), OK),
+    (dict(Sq=0, q=None, o=None), OK),
+    (dict(Sq=300, Skv=299, flags=8), SHAPE),       # causal needs Skv >= Sq
+    (dict(Sq=300, Skv=299, flags=0, q=None), NULL),
+    (dict(Skv=1 << 23), SHAPE),
+    (dict(B=1 << 12, H=1 << 12, Sq=64), SHAPE),    # grid with the maximum split count overflows
+    (dict(k=None), NULL),
+    (dict(v=P + 4), ALIGN),
+    (dict(tile_m=128, tile_n=128), TILE),          # the general kernel has no 128-row K/V tile
+    (dict(tile_m=0, tile_n=64), TILE),
+    (dict(scale=math.inf), SCALE),
+    (dict(splits=-1), SPLITS),
+    (dict(splits=129), SPLITS),
+    (dict(splits=2, ws=None), WORKSPACE),
+    (dict(splits=2, ws=P + 8, ws_bytes=1 << 30), WORKSPACE),
+    (dict(splits=4, ws=P, ws_bytes=4 * 2 * 4 * 5 * 66 * 4 - 1), WORKSPACE),
+])
+def test_kv_entry_point_validation_order_and_codes(lib, kwargs, expect):
+    a = dict(q=P, k=P, v=P, o=P, lse=None, B=2, H=4, Sq=5, Skv=700, D=64, scale=0.125, dtype=1,
+             stream=None, tile_m=0, tile_n=0, flags=0, splits=1, ws=None, ws_bytes=0)
+    a.update(kwargs)
+    st = binding.tiled_sdpa_fwd_kv(a["q"], a["k"], a["v"], a["o"], a["lse"], a["B"], a["H"], a["Sq"], a["Skv"],
+                                   a["D"], a["scale"], a["dtype"], a["stream"], a["tile_m"], a["tile_n"],
+                                   a["flags"], a["splits"], a["ws"], a["ws_bytes"])
+    assert st == expect, binding.status_string(st)
+
+
+def test_kv_workspace_size_and_default_splits(lib):
+    assert binding.kv_workspace_bytes(2, 4, 5, 64, 1) == 0
+    assert binding.kv_workspace_bytes(2, 4, 5, 64, 0) == 0
+    assert binding.kv_workspace_bytes(2, 4, 5, 64, 4) == 2 * 4 * 4 * 5 * (64 + 2) * 4
+    assert binding.kv_workspace_bytes(-1, 4, 5, 64, 4) == 0
+    # enough query tiles: no split; a single decoding query over a long cache: split, but never into
+    # runs shorter than four tiles, never more than the maximum
+    assert binding.kv_default_splits(4, 16, 4096, 4096, 128, binding.BF16) == 1
+    n = binding.kv_default_splits(1, 8, 1, 16384, 128, binding.BF16)
+    assert 2 <= n <= 64 and 16384 // 64 // n >= 4
+    assert binding.kv_default_splits(1, 1, 1, 100, 64, binding.F16) == 1
+    assert binding.kv_default_splits(1, 1, 1, 1 << 20, 64, binding.F16) <= 128
+    with pytest.raises(binding.TiledSdpaError):
+        binding.kv_default_splits(1, 1, 8, 4, 64, binding.F16, binding.FLAG_CAUSAL)
 
 
 def test_probe_validates_before_touching_the_gpu(lib):

@@ -1,0 +1,184 @@
+"""Parity of the Sq x Skv / split-KV entry point (through the C-ABI) against the float64 CPU oracle.
+
+Same tolerances as the square problem: max-abs FP16 2e-3, BF16 1.6e-2, finite output; LSE 1e-4.
+The split count must not change the result beyond rounding: the merged states of Eqs. 2-4 over
+disjoint key ranges are the same sums in another order.
+"""
+import math
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import sdpa_oracle as orc
+from paper_2603_01960_amd import binding
+from paper_2603_01960_amd.workloads import make_qkv, sample_rows
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f16": 2e-3, "bf16": 1.6e-2}
+LSE_TOL = 1e-4
+KV_TILES = [(64, 32), (64, 64), (128, 32), (128, 64)]
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _device():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    binding.load_library()
+    yield
+    torch.cuda.synchronize()
+
+
+def make_q_kv(B, H, Sq, Skv, D, dtype, seed, std=1.0):
+    q = make_qkv(B, H, Sq, D, dtype, seed=seed, qk_std=std)[0]
+    _, k, v = make_qkv(B, H, Skv, D, dtype, seed=seed + 1, qk_std=std)
+    return q, k, v
+
+
+def check_kv(q, k, v, dtype, *, causal=False, splits=0, tile=None, scale=None, rows=None, flags=0, tag=""):
+    say(f"[case] {tag} q={tuple(q.shape)} kv={tuple(k.shape)} dtype={dtype} causal={causal} splits={splits} "
+        f"tile={tile} scale={scale} rows={'all' if rows is None else len(rows)}")
+    o, lse = binding.sdpa_kv(q.cuda(), k.cuda(), v.cuda(), causal=causal, scale=scale, splits=splits,
+                             return_lse=True, tile=tile, flags=flags)
+    torch.cuda.synchronize()
+    o, lse = o.cpu(), lse.cpu()
+    assert torch.isfinite(o.float()).all(), "non-finite output"
+    assert torch.isfinite(lse).all(), "non-finite lse"
+    ref_o, ref_lse = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy(),
+                              scale=scale, rows=rows, return_lse=True, causal=causal)
+    got_o, got_lse = o.double().numpy(), lse.double().numpy()
+    if rows is not None:
+        got_o, got_lse = got_o[:, :, rows], got_lse[:, :, rows]
+    err = float(np.abs(got_o - ref_o).max()) if got_o.size else 0.0
+    lerr = float(np.abs(got_lse - ref_lse).max()) if got_lse.size else 0.0
+    say(f"        max|dO|={err:.3e} (tol {TOL[dtype]:.1e})  max|dLSE|={lerr:.3e}")
+    assert err <= TOL[dtype], f"{tag}: output error {err}"
+    assert lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16.0), f"{tag}: lse error {lerr}"
+    return o, lse
+
+
+# ------------------------------------------------------------------ shapes x splits x tiles
+@pytest.mark.parametrize("tile", KV_TILES)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("D", [64, 128])
+def test_decode_and_chunk_shapes_every_tile(D, dtype, tile):
+    # one query, a few, a ragged tile of them, more queries than keys; key lengths around tile edges
+    for Sq, Skv in ((1, 1), (1, 65), (1, 700), (3, 257), (17, 130), (64, 64), (100, 333), (130, 97), (200, 1000)):
+        q, k, v = make_q_kv(2, 2, Sq, Skv, D, dtype, seed=9000 + Sq + Skv)
+        for splits in (1, 3):
+            check_kv(q, k, v, dtype, splits=splits, tile=tile, tag="kv shapes")
+            if Skv >= Sq:
+                check_kv(q, k, v, dtype, causal=True, splits=splits, tile=tile, tag="kv shapes causal")
+
+
+@pytest.mark.parametrize("splits", [0, 1, 2, 5, 8, 16, 37, 128])
+def test_split_counts_including_more_splits_than_tiles(splits):
+    q, k, v = make_q_kv(1, 3, 5, 1237, 128, "bf16", seed=9100)          # 20 tiles of 64, ragged tail
+    check_kv(q, k, v, "bf16", splits=splits, tag="split count")
+    check_kv(q, k, v, "bf16", splits=splits, causal=True, tag="split count causal")
+    q, k, v = make_q_kv(1, 2, 300, 300, 64, "f16", seed=9101)           # square: splits past the diagonal are empty
+    check_kv(q, k, v, "f16", splits=splits, causal=True, tile=(128, 32), tag="square causal split")
+
+
+@pytest.mark.parametrize("D", [96, 160])
+def test_other_head_dims(D):
+    q, k, v = make_q_kv(1, 2, 9, 777, D, "bf16", seed=9200 + D)
+    check_kv(q, k, v, "bf16", splits=4, tag=f"D={D}")
+    check_kv(q, k, v, "bf16", splits=4, causal=True, tile=(64, 64), tag=f"D={D} causal")
+    q, k, v = make_q_kv(1, 2, 150, 400, D, "f16", seed=9210 + D)
+    check_kv(q, k, v, "f16", splits=3, causal=True, tag=f"D={D} chunk")
+
+
+def test_square_problem_agrees_with_the_plain_entry_point():
+    """Sq = Skv, one split: the general kernel computes what tiled_sdpa_fwd_ex computes, bit for bit."""
+    for causal in (False, True):
+        q, k, v = make_qkv(2, 2, 500, 128, "bf16", seed=9300)
+        qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+        o1, l1 = binding.sdpa(qd, kd, vd, causal=causal, return_lse=True, tile=(128, 64))
+        o2, l2 = binding.sdpa_kv(qd, kd, vd, causal=causal, return_lse=True, tile=(128, 64), splits=1)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2) and torch.equal(l1, l2)
+
+
+def test_split_count_changes_the_result_only_by_rounding():
+    q, k, v = make_q_kv(2, 4, 4, 4096, 128, "f16", seed=9400)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    base = binding.sdpa_kv(qd, kd, vd, splits=1).float()
+    for n in (2, 4, 16):
+        o = binding.sdpa_kv(qd, kd, vd, splits=n).float()
+        torch.cuda.synchronize()
+        assert (o - base).abs().max().item() <= 2 * 2.0 ** -11 * max(1.0, base.abs().max().item())
+
+
+def test_decode_step_equals_last_rows_of_square_causal_attention():
+    """The device's own consistency: the last rows of square causal attention = those rows as a
+    chunk against the whole cache (oracle-checked separately above)."""
+    q, k, v = make_qkv(1, 4, 1000, 128, "bf16", seed=9500)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    full = binding.sdpa(qd, kd, vd, causal=True)
+    tail = binding.sdpa_kv(qd[:, :, -7:].contiguous(), kd, vd, causal=True, splits=4)
+    torch.cuda.synchronize()
+    assert (full[:, :, -7:].float() - tail.float()).abs().max().item() <= 1.6e-2
+    check_kv(q[:, :, -7:].contiguous(), k, v, "bf16", causal=True, splits=4, tag="decode tail")
+
+
+def test_scale_flags_and_caller_owned_buffers():
+    q, k, v = make_q_kv(1, 2, 33, 900, 64, "f16", seed=9600)
+    for scale in (0.0, -0.25, 0.5):
+        check_kv(q, k, v, "f16", scale=scale, splits=3, tag=f"scale={scale}")
+    check_kv(q, k, v, "f16", splits=3, flags=binding.FLAG_EXACT_MAX, tag="exact max")
+    check_kv(q, k, v, "f16", splits=3, flags=binding.FLAG_LINEAR_GRID, causal=True, tag="linear grid")
+    # caller-owned workspace, larger than needed and pre-filled with NaN: every read slot is written first
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    need = binding.kv_workspace_bytes(1, 2, 33, 64, 5)
+    ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    out = torch.full_like(qd, float("nan"))
+    o = binding.sdpa_kv(qd, kd, vd, splits=5, workspace=ws, out=out)
+    torch.cuda.synchronize()
+    assert o.data_ptr() == out.data_ptr() and torch.isfinite(o.float()).all()
+    ref = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy())
+    assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["f16"]
+    assert torch.isnan(ws[need // 4:]).all(), "wrote past the stated workspace size"
+    with pytest.raises(binding.TiledSdpaError):
+        binding.sdpa_kv(qd, kd, vd, splits=5, workspace=ws[: need // 4 - 1])
+
+
+def test_nothing_is_read_past_the_end_of_the_cache():
+    """K and V sit inside larger NaN-filled buffers: a fetch past row Skv would poison the output."""
+    B, H, Sq, Skv, D = 1, 3, 2, 333, 128
+    q, k, v = make_q_kv(B, H, Sq, Skv, D, "bf16", seed=9700)
+    pad = 4096
+    kbuf = torch.full((B * H * Skv * D + 2 * pad,), float("nan"), dtype=torch.bfloat16, device="cuda")
+    vbuf = torch.full_like(kbuf, float("nan"))
+    kd = kbuf[pad:pad + B * H * Skv * D].view(B, H, Skv, D)
+    vd = vbuf[pad:pad + B * H * Skv * D].view(B, H, Skv, D)
+    kd.copy_(k)
+    vd.copy_(v)
+    # the last head is followed by NaN; earlier heads are followed by the next head's rows, which
+    # must not leak in either: compared against the oracle below
+    for splits in (1, 4):
+        o = binding.sdpa_kv(q.cuda(), kd, vd, splits=splits, tile=(64, 64))
+        torch.cuda.synchronize()
+        assert torch.isfinite(o.float()).all()
+        ref = orc.sdpa(q.float().numpy(), k.float().numpy(), v.float().numpy())
+        assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ decoding at full size, sampled rows
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_long_cache_decode_full_size(dtype):
+    # one new token per sequence against a 16384-entry cache (the length of the paper's longest
+    # workload), and a 64-token chunk; heuristic splits
+    for Sq in (1, 64):
+        q, k, v = make_q_kv(2, 8, Sq, 16384, 128, dtype, seed=9800 + Sq)
+        check_kv(q, k, v, dtype, causal=True, tag="long cache")
+    q, k, v = make_q_kv(1, 2, 8192, 8192, 128, dtype, seed=9810, std=math.sqrt(2.0))
+    rows = sample_rows(8192, limit=24)
+    check_kv(q, k, v, dtype, rows=rows, tag="few heads, long sequence")
+    check_kv(q, k, v, dtype, rows=rows, causal=True, tag="few heads, long sequence, causal")
