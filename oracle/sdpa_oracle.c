@@ -134,3 +134,120 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
 {
     return sdpa_oracle_rows_kv(q, k, v, BH, S, S, D, scale, rows, nrows, causal, o, lse, p);
 }
+
+/*
+ * Backward pass (the paper's roadmap, Section 8, names it as future work and prints no formula):
+ * the gradient of the scalar  Lambda = sum_{i,d} dO_id * O_id  with O from Eq. 1 (Section 3.1),
+ * with respect to Q, K and V, written out row by row in float64.  Differentiating Eq. 1
+ * (P = row softmax of the scaled, masked scores, O = P V):
+ *
+ *     dV_jd = sum_i P_ij dO_id
+ *     dP_ij = sum_d dO_id V_jd
+ *     dS_ij = P_ij (dP_ij - sum_j' P_ij' dP_ij')        (Jacobian of the row softmax)
+ *     dQ_id = scale * sum_j dS_ij K_jd
+ *     dK_jd = scale * sum_i dS_ij Q_id
+ *
+ * Masked keys (j > i under the causal mask of Section 4.1.3) have P_ij = 0 and drop out of every sum.
+ * Pass 1 walks query rows (P_i, dP_i, the inner sum, dQ_i; keeps M_i, L_i and the inner sum), pass 2
+ * walks key rows and recomputes P_ij = exp(s_ij - M_i) / L_i for every query i.  Nothing is tiled.
+ *
+ * q, k, v, dout: float32 [BH, S, D] holding 16-bit-rounded values exactly.  qrows / krows select the
+ * rows for which dQ / (dK, dV) are produced (NULL = all S): dq is [BH, nq, D], dk and dv are
+ * [BH, nk, D], all double.  Returns 0 or a negative error as sdpa_oracle_rows does.
+ */
+int sdpa_oracle_bwd(const float *q, const float *k, const float *v, const float *dout,
+                    long BH, long S, long D, double scale, int causal,
+                    const long *qrows, long nq, const long *krows, long nk,
+                    double *dq, double *dk, double *dv)
+{
+    if (!q || !k || !v || !dout || !dq || !dk || !dv) return -1;
+    if (BH < 0 || S < 0 || D <= 0) return -2;
+    if (!qrows) nq = S;
+    if (!krows) nk = S;
+    if (nq < 0 || nk < 0) return -2;
+    if (BH == 0 || S == 0) return 0;
+    for (long r = 0; qrows && r < nq; ++r) if (qrows[r] < 0 || qrows[r] >= S) return -3;
+    for (long r = 0; krows && r < nk; ++r) if (krows[r] < 0 || krows[r] >= S) return -3;
+
+    /* per query row: maximum M, normaliser L and inner = sum_j P_ij dP_ij */
+    double *Mx = (double *)malloc((size_t)BH * S * sizeof(double));
+    double *Lx = (double *)malloc((size_t)BH * S * sizeof(double));
+    double *In = (double *)malloc((size_t)BH * S * sizeof(double));
+    long *qslot = (long *)malloc((size_t)S * sizeof(long));   /* row -> position in qrows, or -1 */
+    if (!Mx || !Lx || !In || !qslot) { free(Mx); free(Lx); free(In); free(qslot); return -4; }
+    for (long i = 0; i < S; ++i) qslot[i] = qrows ? -1 : i;
+    for (long r = 0; qrows && r < nq; ++r) qslot[qrows[r]] = r;
+
+    int failed = 0;
+#pragma omp parallel
+    {
+        double *p = (double *)malloc((size_t)S * sizeof(double));
+        double *dp = (double *)malloc((size_t)S * sizeof(double));
+        if (!p || !dp) {
+#pragma omp atomic write
+            failed = 1;
+        }
+        /* pass 1: query rows */
+#pragma omp for schedule(dynamic, 4)
+        for (long t = 0; t < BH * S; ++t) {
+            if (!p || !dp) continue;
+            const long bh = t / S, i = t % S;
+            const float *qi = q + (bh * S + i) * D, *doi = dout + (bh * S + i) * D;
+            const float *kb = k + bh * S * D, *vb = v + bh * S * D;
+            const long J = causal ? i + 1 : S;
+            double M = -INFINITY;
+            for (long j = 0; j < J; ++j) {
+                double dot = 0.0, dd = 0.0;
+                for (long d = 0; d < D; ++d) {
+                    dot += (double)qi[d] * (double)kb[j * D + d];
+                    dd += (double)doi[d] * (double)vb[j * D + d];
+                }
+                p[j] = scale * dot;
+                dp[j] = dd;
+                if (p[j] > M) M = p[j];
+            }
+            double L = 0.0;
+            for (long j = 0; j < J; ++j) { p[j] = exp(p[j] - M); L += p[j]; }
+            double inner = 0.0;
+            for (long j = 0; j < J; ++j) { p[j] /= L; inner += p[j] * dp[j]; }
+            Mx[t] = M; Lx[t] = L; In[t] = inner;
+            if (qslot[i] >= 0) {
+                double *dqi = dq + (bh * nq + qslot[i]) * D;
+                for (long d = 0; d < D; ++d) dqi[d] = 0.0;
+                for (long j = 0; j < J; ++j) {
+                    const double ds = p[j] * (dp[j] - inner);
+                    for (long d = 0; d < D; ++d) dqi[d] += ds * (double)kb[j * D + d];
+                }
+                for (long d = 0; d < D; ++d) dqi[d] *= scale;
+            }
+        }
+        /* pass 2: key rows (the implicit barrier of the loop above has made M, L, inner visible) */
+#pragma omp for schedule(dynamic, 4)
+        for (long t = 0; t < BH * nk; ++t) {
+            const long bh = t / nk, r = t % nk;
+            const long j = krows ? krows[r] : r;
+            const float *kj = k + (bh * S + j) * D, *vj = v + (bh * S + j) * D;
+            double *dkj = dk + t * D, *dvj = dv + t * D;
+            for (long d = 0; d < D; ++d) { dkj[d] = 0.0; dvj[d] = 0.0; }
+            for (long i = causal ? j : 0; i < S; ++i) {     /* queries that see key j */
+                const float *qi = q + (bh * S + i) * D, *doi = dout + (bh * S + i) * D;
+                double dot = 0.0, dd = 0.0;
+                for (long d = 0; d < D; ++d) {
+                    dot += (double)qi[d] * (double)kj[d];
+                    dd += (double)doi[d] * (double)vj[d];
+                }
+                const double pij = exp(scale * dot - Mx[bh * S + i]) / Lx[bh * S + i];
+                const double ds = pij * (dd - In[bh * S + i]);
+                for (long d = 0; d < D; ++d) {
+                    dkj[d] += ds * (double)qi[d];
+                    dvj[d] += pij * (double)doi[d];
+                }
+            }
+            for (long d = 0; d < D; ++d) dkj[d] *= scale;
+        }
+        free(p);
+        free(dp);
+    }
+    free(Mx); free(Lx); free(In); free(qslot);
+    return failed ? -4 : 0;
+}

@@ -3,7 +3,8 @@
 Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
 this module; the product path never does, and the two share no code.
 
-Three independent float64 routines live here:
+Three independent float64 routines for the forward pass live here (and two for the backward
+pass, :func:`sdpa_bwd` in C and :func:`sdpa_bwd_numpy`, described at the end):
 
 * :func:`sdpa` -- ctypes front end of ``sdpa_oracle.c`` (plain C + OpenMP), the
   materialised row-by-row definition of the paper's Eq. 1 (Section 3.1) with
@@ -55,6 +56,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double,
             ctypes.c_void_p, ctypes.c_long, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.sdpa_oracle_bwd.restype = ctypes.c_int
+        lib.sdpa_oracle_bwd.argtypes = [
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_long, ctypes.c_long, ctypes.c_long, ctypes.c_double, ctypes.c_int,
+            ctypes.c_void_p, ctypes.c_long, ctypes.c_void_p, ctypes.c_long,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.sdpa_oracle_num_threads.restype = ctypes.c_int
         _lib = lib
@@ -191,3 +198,64 @@ def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False, causal=
     if return_lse:
         return out, m + np.log(l)
     return out
+
+
+def sdpa_bwd(q, k, v, dout, scale=None, causal=False, qrows=None, krows=None):
+    """Gradients of sum(dout * O) with respect to q, k, v for O of Eq. 1 (Section 3.1), float64, through
+    the row-by-row C routine ``sdpa_oracle_bwd`` (the paper leaves the backward pass as future work,
+    Section 8, so the formulas are the derivative of Eq. 1 written out; see the C source).
+
+    q, k, v, dout: [..., S, D] with equal shapes.  ``qrows`` / ``krows`` optionally select the rows
+    for which dq / (dk, dv) are returned.  Returns (dq [..., nq, D], dk [..., nk, D], dv [..., nk, D]).
+    """
+    q32, k32, v32, d32 = _as_f32(q), _as_f32(k), _as_f32(v), _as_f32(dout)
+    if not (q32.shape == k32.shape == v32.shape == d32.shape) or q32.ndim < 2:
+        raise ValueError("q, k, v, dout must have identical shape [..., S, D]")
+    lead, (S, D) = q32.shape[:-2], q32.shape[-2:]
+    BH = int(np.prod(lead, dtype=np.int64)) if lead else 1
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    scale = float(np.float32(scale))
+
+    def subset(rows):
+        if rows is None:
+            return None, S, None
+        arr = np.ascontiguousarray(rows, dtype=np.int64)
+        if arr.ndim != 1:
+            raise ValueError("row subsets must be one-dimensional")
+        return arr, arr.size, arr.ctypes.data
+
+    qarr, nq, qptr = subset(qrows)
+    karr, nk, kptr = subset(krows)
+    dq = np.zeros((BH, nq, D), dtype=np.float64)
+    dk = np.zeros((BH, nk, D), dtype=np.float64)
+    dv = np.zeros((BH, nk, D), dtype=np.float64)
+    rc = _load().sdpa_oracle_bwd(q32.ctypes.data, k32.ctypes.data, v32.ctypes.data, d32.ctypes.data,
+                                 BH, S, D, scale, 1 if causal else 0, qptr, nq, kptr, nk,
+                                 dq.ctypes.data, dk.ctypes.data, dv.ctypes.data)
+    if rc != 0:
+        raise RuntimeError(f"sdpa_oracle_bwd failed with status {rc}")
+    return dq.reshape(*lead, nq, D), dk.reshape(*lead, nk, D), dv.reshape(*lead, nk, D)
+
+
+def sdpa_bwd_numpy(q, k, v, dout, scale=None, causal=False):
+    """The same gradients as numpy float64 matrix expressions (small shapes): with P the row softmax
+    of the scaled, masked scores, dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(P * dP)),
+    dQ = scale * dS K, dK = scale * dS^T Q."""
+    q64, k64, v64, d64 = (np.asarray(x, dtype=np.float64) for x in (q, k, v, dout))
+    D = q64.shape[-1]
+    if scale is None:
+        scale = 1.0 / np.sqrt(np.float64(D))
+    scale = float(np.float32(scale))
+    s = scale * (q64 @ np.swapaxes(k64, -1, -2))
+    if causal:
+        S = s.shape[-1]
+        s = s + np.where(np.arange(S)[None, :] > np.arange(S)[:, None], -np.inf, 0.0)
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    p = e / e.sum(axis=-1, keepdims=True)
+    dv = np.swapaxes(p, -1, -2) @ d64
+    dp = d64 @ np.swapaxes(v64, -1, -2)
+    ds = p * (dp - (p * dp).sum(axis=-1, keepdims=True))
+    dq = scale * (ds @ k64)
+    dk = scale * (np.swapaxes(ds, -1, -2) @ q64)
+    return dq, dk, dv
