@@ -40,8 +40,8 @@ enum {
                                     tile_n = 128 at D = 160 (does not fit the LDS)          */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
-    TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split: workspace NULL, not 16-byte
-                                    aligned, or smaller than tiled_sdpa_kv_workspace_bytes reports */
+    TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split, tiled_sdpa_bwd: workspace NULL,
+                                    not 16-byte aligned, or smaller than the matching *_workspace_bytes reports */
     TSDPA_ERR_BAD_SPLITS = 10    /* splits < 0 or > TSDPA_MAX_SPLITS                         */
 };
 
@@ -131,6 +131,34 @@ int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype
 /* Workspace bytes tiled_sdpa_fwd_kv needs for `splits` >= 1 (a value from tiled_sdpa_kv_default_splits,
  * or the caller's own): B*H*splits*Sq*(D+2) floats.  0 for splits <= 1 or negative arguments. */
 unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, int splits);
+
+/*
+ * Backward pass: gradients of a scalar loss with respect to q, k and v, given dout = d(loss)/d(o).
+ * The paper leaves the backward pass as future work (Section 8); this is the derivative of its
+ * Eq. 1 (Section 3.1), evaluated tile by tile with the probabilities recomputed from the forward
+ * pass's log-sum-exp (never stored), in FP32 with 16-bit MFMA operands as in Section 4.1.3:
+ *     P = exp(scale * Q K^T [+ causal mask] - lse),  dV = P^T dO,  dP = dO V^T,
+ *     dS = P * (dP - rowsum(dO * O)),  dQ = scale * dS K,  dK = scale * dS^T Q.
+ *
+ *   q, k, v, o, dout : [B, H, S, D] as for tiled_sdpa_fwd; o and lse are that call's outputs for the
+ *                      same q, k, v, scale and flags (lse is required here).
+ *   dq, dk, dv       : [B, H, S, D], same type; every element is overwritten.  Must not alias inputs.
+ *   D                : 64 or 128 (other head dims: TSDPA_ERR_UNSUPPORTED_D).
+ *   flags            : TSDPA_FLAG_CAUSAL or 0.
+ *   workspace        : device memory, 16-byte aligned, at least tiled_sdpa_bwd_workspace_bytes(B, H, S)
+ *                      bytes (two FP32 values per query row); caller-owned, used only during this call's
+ *                      kernels, so calls that may overlap on the GPU need distinct workspaces.
+ * Three kernels are enqueued on `stream`: row statistics, then (dK, dV), then dQ.  No sum crosses
+ * workgroups, so results are deterministic.  Validation order: dtype, D, shape, empty problem, null
+ * pointers, alignment, scale, workspace, launch.
+ */
+int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, const void *dout,
+                   const float *lse, void *dq, void *dk, void *dv,
+                   int B, int H, int S, int D, float scale, int dtype, unsigned flags,
+                   void *workspace, unsigned long long workspace_bytes, void *stream);
+
+/* Workspace bytes tiled_sdpa_bwd needs: 2 * (B*H*S + 128) floats.  0 for negative arguments. */
+unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S);
 
 /*
  * Measurement aid, not part of the attention path: enqueue a register-resident stream of

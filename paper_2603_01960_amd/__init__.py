@@ -5,6 +5,6 @@ The compute path is the HIP library ``libtiled_sdpa.so`` built from ``csrc/``;
 draws seeded inputs.
 """
 from .binding import (  # noqa: F401
-    F16, BF16, TiledSdpaError, kv_default_splits, kv_workspace_bytes, library_path, load_library,
+    F16, BF16, TiledSdpaError, bwd_workspace_bytes, sdpa_backward, tiled_sdpa_bwd, kv_default_splits, kv_workspace_bytes, library_path, load_library,
     probe_mfma, sdpa, sdpa_kv, status_string, tiled_sdpa_fwd, tiled_sdpa_fwd_ex, tiled_sdpa_fwd_kv, version,
 )

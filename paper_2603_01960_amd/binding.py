@@ -22,6 +22,8 @@ _lib = None
 EXPORTS = (
     "tiled_sdpa_fwd",
     "tiled_sdpa_fwd_ex",
+    "tiled_sdpa_bwd",
+    "tiled_sdpa_bwd_workspace_bytes",
     "tiled_sdpa_default_tile",
     "tiled_sdpa_fwd_kv",
     "tiled_sdpa_kv_default_splits",
@@ -66,6 +68,10 @@ def load_library():
     lib.tiled_sdpa_kv_default_splits.argtypes = [ci, ci, ci, ci, ci, ci, ctypes.c_uint, ctypes.POINTER(ci)]
     lib.tiled_sdpa_kv_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_kv_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    lib.tiled_sdpa_bwd.restype = ci
+    lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
+    lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
+    lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
     lib.tiled_sdpa_probe_mfma.restype = ci
     lib.tiled_sdpa_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tiled_sdpa_status_string.restype = ctypes.c_char_p
@@ -181,6 +187,56 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return (out, lse) if return_lse else out
+
+
+def bwd_workspace_bytes(B: int, H: int, S: int) -> int:
+    return int(load_library().tiled_sdpa_bwd_workspace_bytes(B, H, S))
+
+
+def tiled_sdpa_bwd(q_ptr, k_ptr, v_ptr, o_ptr, dout_ptr, lse_ptr, dq_ptr, dk_ptr, dv_ptr, B, H, S, D, scale,
+                   dtype, flags, workspace_ptr, workspace_bytes, stream) -> int:
+    return int(load_library().tiled_sdpa_bwd(q_ptr, k_ptr, v_ptr, o_ptr, dout_ptr, lse_ptr, dq_ptr, dk_ptr,
+                                             dv_ptr, B, H, S, D, float(scale), dtype, flags,
+                                             workspace_ptr, workspace_bytes, stream))
+
+
+def sdpa_backward(q, k, v, o, dout, lse, causal: bool = False, scale=None, *, workspace=None, grads=None):
+    """(dq, dk, dv) for the attention of :func:`sdpa`; ``o`` and ``lse`` are that call's outputs
+    (``return_lse=True``) for the same q, k, v, causal and scale.  ``grads=(dq, dk, dv)`` and
+    ``workspace`` let the caller own the buffers; otherwise torch allocates them."""
+    import torch
+
+    for name, t in (("q", q), ("k", k), ("v", v), ("o", o), ("dout", dout)):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda:
+            raise ValueError(f"{name} must be a device tensor")
+        if t.dim() != 4 or not t.is_contiguous():
+            raise ValueError(f"{name} must be contiguous [B, H, S, D]")
+        if t.shape != q.shape or t.dtype != q.dtype or t.device != q.device:
+            raise ValueError("q, k, v, o, dout must agree in shape, dtype and device")
+    if q.dtype not in (torch.float16, torch.bfloat16):
+        raise ValueError("dtype must be float16 or bfloat16")
+    B, H, S, D = q.shape
+    if lse.shape != (B, H, S) or lse.dtype != torch.float32 or not lse.is_contiguous() or lse.device != q.device:
+        raise ValueError("lse must be contiguous float32 [B, H, S] on the same device")
+    dtype = F16 if q.dtype == torch.float16 else BF16
+    if grads is None:
+        grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q))
+    for gname, t in zip(("dq", "dk", "dv"), grads):
+        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous() or t.device != q.device:
+            raise ValueError(f"{gname} must match q in shape, dtype, device and be contiguous")
+    need = bwd_workspace_bytes(B, H, S)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_bytes = workspace.numel() * workspace.element_size()
+    with torch.cuda.device(q.device):
+        stream = torch.cuda.current_stream().cuda_stream
+        st = tiled_sdpa_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), dout.data_ptr(),
+                            lse.data_ptr(), grads[0].data_ptr(), grads[1].data_ptr(), grads[2].data_ptr(),
+                            B, H, S, D, math.nan if scale is None else scale, dtype,
+                            FLAG_CAUSAL if causal else 0, workspace.data_ptr(), ws_bytes, stream)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return grads
 
 
 def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False, out=None,

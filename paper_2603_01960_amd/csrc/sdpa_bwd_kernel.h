@@ -1,0 +1,332 @@
+// Backward pass of tiled SDPA for gfx950 (MI355X).  The paper leaves it as future work (Section 8);
+// what is computed is the derivative of its Eq. 1 (Section 3.1), with P recomputed tile by tile from
+// the forward pass's log-sum-exp instead of being stored, in the spirit of Section 4.1.2:
+//
+//     P_ij  = exp(scale * <q_i, k_j> - LSE_i)          (0 for masked keys)
+//     dV_j  = sum_i P_ij dO_i
+//     dP_ij = <dO_i, v_j>
+//     dS_ij = P_ij (dP_ij - Delta_i),   Delta_i = <dO_i, O_i>   (= sum_j P_ij dP_ij)
+//     dQ_i  = scale * sum_j dS_ij k_j,  dK_j = scale * sum_i dS_ij q_i
+//
+// Two passes over the S x S score plane, both instances of ONE kernel template, so that no sum
+// crosses workgroups (no atomics, deterministic results):
+//   * QUERIES resident (KEYS_RES = false): a workgroup owns 32*NW query rows (Q and dO rows in
+//     registers), streams K and V tiles, produces dQ;
+//   * KEYS resident (KEYS_RES = true): a workgroup owns 32*NW key rows (K and V rows in registers),
+//     streams Q and dO tiles, produces dK and dV.
+// With R the resident and T the streamed rows, both passes compute, per streamed tile,
+//     acc[t][r]  = <T1_t, R1_r>  (scores)        acc2[t][r] = <T2_t, R2_r>  (dP)
+//     out1^T[d][r] += sum_t T1[t][d] dS[t][r]    (dQ^T or dK^T)
+//     out2^T[d][r] += sum_t T2[t][d] P[t][r]     (dV^T; keys-resident pass only)
+// (T1, T2, R1, R2) = (K, V, Q, dO) or (Q, dO, K, V).  The MFMA formulation is the forward kernel's:
+// transposed accumulators (a lane owns one resident row), P and dS handed to the second product
+// straight from the accumulator registers as B-operands, the streamed tile read row-wise for the
+// first product and through the transposing LDS read for the second.  Since one LDS tile now serves
+// both kinds of read, its 16-byte chunks are XOR-swizzled by a function of the row under which
+// both are bank-conflict free (BwdGeom::swz).
+#pragma once
+#include "sdpa_fwd_kernel.h"
+#include "sdpa_fwd_launch.h"
+
+namespace tsdpa {
+
+// LDS geometry of a streamed tile: TS rows of D 16-bit values, rows DG*2 bytes apart.  Chunk c of row
+// r sits at c ^ swz(r).  Row-wise reads have 16 lanes fetch one chunk index of 16 consecutive rows:
+// swz is a bijection of the row bits that select the bank group, so they spread over all banks.
+// Transposing reads have 32 lanes fetch one 64-byte block (4 chunks) of 4 consecutive rows: bits
+// 3:2 of swz (bit 2 when a row has only two blocks) come from the low row bits, so the four rows
+// land in different blocks.
+template <int D, int TS> struct BwdGeom {
+    static_assert(D == 64 || D == 128, "backward pass: head dims 64 and 128");
+    static constexpr int DG = D;
+    static constexpr int ROW = DG * 2;
+    static constexpr int TILE = TS * ROW;
+    static constexpr int LDS_BYTES = 4 * TILE;      // T1 slots 0,1 then T2 slots 0,1
+    static __host__ __device__ constexpr int swz(int r) {
+        return DG == 64 ? ((((r >> 1) & 1) << 2) | ((r >> 2) & 3)) : (((r & 3) << 2) | ((r >> 2) & 3));
+    }
+};
+
+// Delta_i = <dO_i, O_i> and LSE_i in log2 units, one row per group of 16 (D <= 128) lanes; the
+// kBwdStatPad entries after the last row are set to zero.
+template <typename T, int D>
+__global__ void __launch_bounds__(256)
+sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, const float *__restrict__ lse,
+                        float *__restrict__ delta, float *__restrict__ lse2, long long rows)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    using vec8 = typename Elem<T>::vec8;
+    constexpr int LPR = 16;                        // lanes per row; lanes >= D/8 idle
+    const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) / LPR;
+    const int part = threadIdx.x % LPR;
+    float sum = 0.f;
+    if (row < rows && part < D / 8) {
+        const vec8 a = *(const vec8 *)(o + row * D + part * 8);
+        const vec8 b = *(const vec8 *)(dout + row * D + part * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sum += (float)a[e] * (float)b[e];
+    }
+#pragma unroll
+    for (int w = LPR / 2; w >= 1; w >>= 1) sum += __shfl_xor(sum, w, LPR);
+    if (part == 0) {
+        if (row < rows) {
+            delta[row] = sum;
+            lse2[row] = lse[row] * 1.44269504088896340736f;
+        } else if (row < rows + kBwdStatPad) {
+            delta[row] = 0.f;
+            lse2[row] = 0.f;
+        }
+    }
+#endif
+}
+
+template <typename T, int D, int NW, int TS, int WPS, bool KEYS_RES>
+__global__ void __launch_bounds__(NW * 64, WPS)
+sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+                const T *__restrict__ dout, const float *__restrict__ lse2, const float *__restrict__ delta,
+                T *__restrict__ out1, T *__restrict__ out2,   // dQ, unused  or  dK, dV
+                int S, int nR, int N, float c, float scale, uint32_t rsign, int causal, unsigned stat_bytes)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    using E = Elem<T>;
+    using vec8 = typename E::vec8;
+    using vec4 = typename E::vec4;
+    using G = BwdGeom<D, TS>;
+    constexpr int RM = NW * 32;                   // resident rows per workgroup
+    constexpr int CPR = G::DG / 8;                // 16-byte chunks per row
+    constexpr int NLD = TS * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
+    static_assert(NLD >= 1 && (TS * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
+    constexpr int NB = TS / 32, KK = D / 16, DB = D / 32;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const lds_ptr lds = (lds_ptr)smem;
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int g = lane >> 5, l32 = lane & 31;
+
+    const int wg = remap_workgroup(blockIdx.x, N, false);
+    const int head = wg / nR;
+    // causal: query tiles get longer with their index, key tiles shorter; start the long ones first
+    const int rt = (causal && !KEYS_RES) ? nR - 1 - (wg - head * nR) : wg - head * nR;
+    const size_t head_off = (size_t)head * (size_t)S * D;
+    const T *r1 = (KEYS_RES ? k : q) + head_off;       // resident operands
+    const T *r2 = (KEYS_RES ? v : dout) + head_off;
+    const T *t1 = (KEYS_RES ? q : k) + head_off;       // streamed operands
+    const T *t2 = (KEYS_RES ? dout : v) + head_off;
+
+    // ---- resident rows as MFMA B-operands: lane holds R[row l32][kk*16 + g*8 .. +7]; the sign of a
+    // negative scale is folded into R1 so that c = |scale| * log2(e) applies to the scores
+    const int r0 = rt * RM;
+    const int rrow = r0 + wave * 32 + l32;
+    const int rrow_c = rrow < S ? rrow : S - 1;
+    vec8 rf1[KK], rf2[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+        u32x4 raw = *(const u32x4 *)(r1 + (size_t)rrow_c * D + kk * 16 + g * 8);
+        raw ^= rsign;
+        rf1[kk] = __builtin_bit_cast(vec8, raw);
+        rf2[kk] = *(const vec8 *)(r2 + (size_t)rrow_c * D + kk * 16 + g * 8);
+    }
+
+    // ---- range of streamed tiles, and the streamed rows [tlo, thi] that pair with this lane's row
+    const int nT = (S + TS - 1) / TS;
+    const int last_row = (r0 + RM < S ? r0 + RM : S) - 1;
+    int j0 = 0, j1 = nT;
+    int tlo = 0, thi = S - 1;
+    if (causal) {
+        if (KEYS_RES) { j0 = r0 / TS; tlo = rrow; }                       // queries at or after the key
+        else { j1 = last_row / TS + 1; thi = rrow < S ? rrow : S - 1; }   // keys up to the query
+    }
+
+    // per-row statistics of the query side: LSE (log2 units) and Delta
+    // (the descriptors span the whole arrays, slack included: a 4-row read never straddles their end;
+    // rows >= S of a head pick up the next head's or the slack's values and are masked)
+    float lse_r = 0.f, delta_r = 0.f;
+    if (!KEYS_RES) { lse_r = lse2[(size_t)head * S + rrow_c]; delta_r = delta[(size_t)head * S + rrow_c]; }
+    const auto lse_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)lse2, (short)0, (int)stat_bytes, 0x00020000);
+    const auto delta_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)delta, (short)0, (int)stat_bytes, 0x00020000);
+    const int stat_soff = head * S * 4;
+
+    // ---- streamed tiles HBM -> LDS, as in the forward kernel: a descriptor per tensor covers this
+    // head's S rows (rows >= S read as zeros), lane `lane` of load `it` fills LDS chunk
+    // (it*NW + wave)*64 + lane with the global chunk the swizzle maps there
+    const auto t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::ROW, 0x00020000);
+    const auto t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::ROW, 0x00020000);
+    int goff[NLD];
+#pragma unroll
+    for (int it = 0; it < NLD; ++it) {
+        const int p = (it * NW + wave) * 64 + lane;
+        const int r = p / CPR, cp = p % CPR;
+        goff[it] = r * G::ROW + ((cp ^ G::swz(r)) << 4);
+    }
+    auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) {
+        const int soff = (j < j1 ? j : nT) * G::TILE;     // a tile past the range: outside the descriptor, zeros
+#pragma unroll
+        for (int it = 0; it < NLD; ++it)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
+                                                     goff[it], soff, 0, 0);
+    };
+    constexpr int T1SLOT0 = 0, T1SLOT1 = G::TILE, T2SLOT0 = 2 * G::TILE, T2SLOT1 = 3 * G::TILE;
+
+    f32x16 o1[DB], o2[KEYS_RES ? DB : 1];
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            o1[db][i] = 0.f;
+            if constexpr (KEYS_RES) o2[db][i] = 0.f;
+        }
+
+    // ---- per-lane LDS read offsets (tile slot, nb, ks enter as immediates)
+    // row-wise: row l32 (+32*nb), chunk (2*kk + g) ^ swz(row)
+    int row_off[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) row_off[kk] = l32 * G::ROW + (((2 * kk + g) ^ G::swz(l32)) << 4);
+    // transposing: row g*4 + (lane%16)/4 (+ multiples of 8), bytes db*64 + ((lane/16)%2)*32 + (lane%4)*8
+    // of the row, i.e. chunk db*4 + ((lane/16)%2)*2 + (lane%4)/2, swizzled.  Adding 8 to the row flips
+    // bit 1 of swz (bit 5 of the byte offset); adding 16 or 32 leaves swz alone.
+    const int t_row = g * 4 + ((lane & 15) >> 2);
+    int tr_off[DB];
+#pragma unroll
+    for (int db = 0; db < DB; ++db) {
+        const int chunk = db * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
+        tr_off[db] = t_row * G::ROW + ((chunk ^ G::swz(t_row)) << 4) + (lane & 1) * 8;
+    }
+
+    // acc[i] = <T_row, R_col>, row = nb*32 + (i/4)*8 + g*4 + i%4 of the tile, col = this lane's row
+    auto products = [&](int slot, int nb, const vec8 (&rf)[KK], f32x16 &acc) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+        for (int kk = 0; kk < KK; ++kk) {
+            u32x4 raw = lds_read128(lds + slot + nb * 32 * G::ROW + row_off[kk]);
+            acc = E::mfma(__builtin_bit_cast(vec8, raw), rf[kk], acc);
+        }
+    };
+    // out^T += T^T X, X taken from accumulator layout as B-operands (k-slots 0..3 / 4..7 of a lane <->
+    // tile rows base+g*4+0..3 / base+8+g*4+0..3, mirrored on the A side by the two transposing reads)
+    auto accumulate = [&](int slot, const vec8 (&xb)[NB][2], f32x16 (&out)[DB]) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int db = 0; db < DB; ++db) {
+                    const lds_ptr p0 = lds + slot + (nb * 32 + ks * 16) * G::ROW;
+                    i16x4 lo = lds_read_tr16(p0 + tr_off[db]);
+                    i16x4 hi = lds_read_tr16(p0 + 8 * G::ROW + (tr_off[db] ^ 32));
+                    i16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    out[db] = E::mfma(__builtin_bit_cast(vec8, a), xb[nb][ks], out[db]);
+                }
+    };
+
+    vec8 xp[KEYS_RES ? NB : 1][2], xds[NB][2];
+
+    auto tile = [&](int j, auto par_tag, auto mask_tag) {
+        constexpr int PAR = decltype(par_tag)::value;
+        constexpr bool MASK = decltype(mask_tag)::value;
+        constexpr int s1 = PAR ? T1SLOT1 : T1SLOT0, s2 = PAR ? T2SLOT1 : T2SLOT0;
+        // statistics of the streamed query rows (keys-resident pass): 4 consecutive rows per load,
+        // issued before the next tile's loads so that waiting for them does not wait for those
+        f32x4 st_lse[KEYS_RES ? NB : 1][4], st_delta[KEYS_RES ? NB : 1][4];
+        if constexpr (KEYS_RES) {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int off = (j * TS + nb * 32 + r4 * 8 + g * 4) * 4;
+                    st_lse[nb][r4] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(lse_rsrc, off, stat_soff, 0));
+                    st_delta[nb][r4] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(delta_rsrc, off, stat_soff, 0));
+                }
+        }
+        load_tile(t1_rsrc, j + 1, lds + (PAR ? T1SLOT0 : T1SLOT1));
+        load_tile(t2_rsrc, j + 1, lds + (PAR ? T2SLOT0 : T2SLOT1));
+        const int trow0 = j * TS + g * 4;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {       // one 32-row block at a time: only its two accumulators are live
+            f32x16 sacc, dpacc;
+            products(s1, nb, rf1, sacc);
+            products(s2, nb, rf2, dpacc);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const float l2 = KEYS_RES ? st_lse[KEYS_RES ? nb : 0][i >> 2][i & 3] : lse_r;
+                const float dl = KEYS_RES ? st_delta[KEYS_RES ? nb : 0][i >> 2][i & 3] : delta_r;
+                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], c, -l2));
+                float ds = p * (dpacc[i] - dl);
+                if constexpr (MASK) {
+                    const int trow = trow0 + nb * 32 + (i >> 2) * 8 + (i & 3);
+                    if (trow < tlo || trow > thi) { p = 0.f; ds = 0.f; }
+                }
+                xds[nb][i >> 3][i & 7] = (T)ds;
+                if constexpr (KEYS_RES) xp[nb][i >> 3][i & 7] = (T)p;
+            }
+        }
+        accumulate(s1, xds, o1);
+        if constexpr (KEYS_RES) accumulate(s2, xp, o2);
+        TSDPA_WAIT_VMCNT0();
+        __syncthreads();
+    };
+
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    // a tile needs the masked path if it reaches past row S-1 or (causal) crosses the diagonal of any
+    // of this workgroup's rows; such tiles sit at the end of the range (queries resident) or at its
+    // start and, for the ragged tail, its end (keys resident).  Unmasked tiles run in pairs.
+    auto needs_mask = [&](int j) -> bool {
+        if ((j + 1) * TS > S) return true;
+        if (!causal) return false;
+        return KEYS_RES ? j * TS < r0 + RM - 1 : (j + 1) * TS - 1 > r0;
+    };
+    if (j0 < j1) {
+        load_tile(t1_rsrc, j0, lds + T1SLOT0);
+        load_tile(t2_rsrc, j0, lds + T2SLOT0);
+        TSDPA_WAIT_VMCNT0();
+        __syncthreads();
+        int j = j0;
+        while (j < j1) {
+            const bool even = ((j - j0) & 1) == 0;
+            if (even && j + 1 < j1 && !needs_mask(j) && !needs_mask(j + 1)) {
+                tile(j, P0{}, std::false_type{});
+                tile(j + 1, P1{}, std::false_type{});
+                j += 2;
+            } else {
+                if (even) tile(j, P0{}, std::true_type{});
+                else      tile(j, P1{}, std::true_type{});
+                ++j;
+            }
+        }
+    }
+
+    // ---- store: out^T tiles are turned through LDS (as the forward kernel's O) and written as whole
+    // rows; dQ and dK carry the factor `scale` of the score, dV none.  The last barrier of the loop
+    // has every wavefront past its last LDS read.
+    auto store = [&](const f32x16 (&acc)[DB], float factor, T *dst) {
+        constexpr int CMASK = CPR - 1;
+        const lds_ptr ow = lds + wave * (32 * G::ROW);
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int q4 = 0; q4 < 4; ++q4) {
+                vec4 val;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[e] = (T)(acc[db][q4 * 4 + e] * factor);
+                const int chunk = db * 4 + q4;
+                *(TSDPA_LDS vec4 *)(ow + l32 * G::ROW + ((chunk ^ (l32 & CMASK)) << 4) + g * 8) = val;
+            }
+        constexpr int RPI = 64 / CPR;
+        const int row0 = r0 + wave * 32;
+#pragma unroll
+        for (int i = 0; i < 32 / RPI; ++i) {
+            const int r = i * RPI + lane / CPR, cc = lane % CPR;
+            const u32x4 val = lds_read128(ow + r * G::ROW + ((cc ^ (r & CMASK)) << 4));
+            if (row0 + r < S) *(u32x4 *)(dst + head_off + (size_t)(row0 + r) * D + cc * 8) = val;
+        }
+    };
+    static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");
+    store(o1, scale, out1);
+    if constexpr (KEYS_RES) store(o2, 1.0f, out2);
+#endif
+}
+
+}  // namespace tsdpa

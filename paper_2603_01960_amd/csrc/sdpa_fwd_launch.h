@@ -22,6 +22,24 @@ struct LaunchArgs {
     hipStream_t stream;
 };
 
+// Rows of slack after the B*H*S entries of each backward statistics array: the keys-resident pass
+// reads them 4 rows at a time up to a tile past the last row of the last head.
+constexpr int kBwdStatPad = 128;
+
+struct BwdLaunchArgs {
+    const void *q, *k, *v, *o, *dout;
+    const float *lse;        // natural-log LSE of the forward pass, [BH, S]
+    void *dq, *dk, *dv;
+    float *delta, *lse2;     // workspace halves: [BH*S + slack] each
+    unsigned stat_bytes;     // bytes of one workspace half
+    int BH, S;
+    float c;                 // |scale| * log2(e)
+    float scale;             // signed scale: factor of dQ and dK
+    uint32_t rsign;          // 0x80008000 when scale < 0 (sign folded into the resident Q or K), else 0
+    int causal;
+    hipStream_t stream;
+};
+
 // Each returns a hipError_t cast to int (0 = success); tile_m in {64,128}, tile_n in {32,64,128}
 // (tile_n in {32,64} when a.kv is set).
 int launch_f16_d64(int tile_m, int tile_n, const LaunchArgs &a);
@@ -32,5 +50,12 @@ int launch_bf16_d64(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_bf16_d96(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_bf16_d128(int tile_m, int tile_n, const LaunchArgs &a);
 int launch_bf16_d160(int tile_m, int tile_n, const LaunchArgs &a);
+
+
+// Backward pass: statistics kernel, then the keys-resident (dK, dV) and queries-resident (dQ) passes.
+int launch_bwd_f16_d64(const BwdLaunchArgs &a);
+int launch_bwd_f16_d128(const BwdLaunchArgs &a);
+int launch_bwd_bf16_d64(const BwdLaunchArgs &a);
+int launch_bwd_bf16_d128(const BwdLaunchArgs &a);
 
 }  // namespace tsdpa

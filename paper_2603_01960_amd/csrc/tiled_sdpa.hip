@@ -266,6 +266,54 @@ int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, floa
     return TSDPA_OK;
 }
 
+unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S)
+{
+    if (B < 0 || H < 0 || S < 0) return 0;
+    return 2ull * ((unsigned long long)B * H * S + tsdpa::kBwdStatPad) * sizeof(float);
+}
+
+int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, const void *dout,
+                   const float *lse, void *dq, void *dk, void *dv,
+                   int B, int H, int S, int D, float scale, int dtype, unsigned flags,
+                   void *workspace, unsigned long long workspace_bytes, void *stream)
+{
+    if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
+    if (D != 64 && D != 128) return TSDPA_ERR_UNSUPPORTED_D;
+    int st = validate_shape(B, H, S, D, dtype);
+    if (st != TSDPA_OK) return st;
+    // the statistics arrays are addressed through a 32-bit byte range
+    if ((int64_t)B * H * S >= ((int64_t)1 << 29)) return TSDPA_ERR_BAD_SHAPE;
+    if ((int64_t)B * H * S == 0) return TSDPA_OK;
+    if (!q || !k || !v || !o || !dout || !lse || !dq || !dk || !dv) return TSDPA_ERR_NULL_PTR;
+    const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o | (uintptr_t)dout |
+                           (uintptr_t)dq | (uintptr_t)dk | (uintptr_t)dv;
+    if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
+    if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
+    if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
+    if (!workspace || ((uintptr_t)workspace & 15u) != 0 ||
+        workspace_bytes < tiled_sdpa_bwd_workspace_bytes(B, H, S))
+        return TSDPA_ERR_WORKSPACE;
+
+    tsdpa::BwdLaunchArgs a{};
+    a.q = q; a.k = k; a.v = v; a.o = o; a.dout = dout; a.lse = lse;
+    a.dq = dq; a.dk = dk; a.dv = dv;
+    const size_t half = (size_t)B * H * S + tsdpa::kBwdStatPad;
+    a.delta = (float *)workspace;
+    a.lse2 = (float *)workspace + half;
+    a.stat_bytes = (unsigned)(half * sizeof(float));
+    a.BH = B * H;
+    a.S = S;
+    a.c = std::fabs(scale) * 1.44269504088896340736f;
+    a.scale = scale;
+    a.rsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
+    a.causal = (flags & TSDPA_FLAG_CAUSAL) ? 1 : 0;
+    a.stream = (hipStream_t)stream;
+    int err;
+    if (dtype == TSDPA_F16) err = D == 64 ? tsdpa::launch_bwd_f16_d64(a) : tsdpa::launch_bwd_f16_d128(a);
+    else err = D == 64 ? tsdpa::launch_bwd_bf16_d64(a) : tsdpa::launch_bwd_bf16_d128(a);
+    return err == 0 ? TSDPA_OK : TSDPA_ERR_LAUNCH;
+}
+
 int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *lse,
                    int B, int H, int S, int D, float scale, int dtype, void *stream)
 {
