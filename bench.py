@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--kv", default=None,
                     help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
     ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
+    ap.add_argument("--bwd", action="store_true",
+                    help="time the backward pass (tiled_sdpa_bwd: statistics, dK/dV and dQ kernels) of the workload")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
@@ -221,6 +223,54 @@ def bench_kv(pkg, torch, args, tile, flags):
         "roofline": roofline}), flush=True)
 
 
+def bench_bwd(pkg, torch, args, flags):
+    """One JSON line for tiled_sdpa_bwd on a workload (its three kernels timed as one step; the forward
+    pass that provides o and lse, the gradients and the workspace are set up outside the timed region)."""
+    from paper_2603_01960_amd.workloads import WORKLOADS, Workload, make_qkv, make_workload
+    if args.shape:
+        B, H, S, D = (int(x) for x in args.shape.split(","))
+        dtype = args.dtype or "bf16"
+        w = Workload("custom", B, H, S, D, (dtype,), 4242, 1.0)
+        q, k, v = make_qkv(B, H, S, D, dtype, seed=w.seed)
+    else:
+        w, q, k, v = make_workload(args.workload, args.dtype)
+        dtype = args.dtype or w.dtypes[0]
+    causal = bool(flags & pkg.binding.FLAG_CAUSAL)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    g = torch.Generator(device="cpu").manual_seed(w.seed + 50)
+    dout = torch.randn(*q.shape, dtype=torch.float32, generator=g).to(q.dtype).cuda()
+    o, lse = pkg.sdpa(qd, kd, vd, causal=causal, return_lse=True)
+    grads = tuple(torch.empty_like(qd) for _ in range(3))
+    ws = torch.empty(pkg.bwd_workspace_bytes(w.B, w.H, w.S), dtype=torch.uint8, device="cuda")
+    run = lambda: pkg.sdpa_backward(qd, kd, vd, o, dout, lse, causal=causal, workspace=ws, grads=grads)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    a.record()
+    for _ in range(args.steps):
+        run()
+    b.record()
+    torch.cuda.synchronize()
+    wall_ms = 1e3 * (time.perf_counter() - t0) / args.steps
+    ms = a.elapsed_time(b) / args.steps
+    assert all(torch.isfinite(t.float()).all().item() for t in grads), "non-finite gradient"
+    # five S x S x D products (scores, dP, dV, dK, dQ) of 2*B*H*S^2*D flops each; half under the causal mask
+    flops = 2.5 * w.flops * (0.5 if causal else 1.0)
+    tf = flops / (ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "SDPA backward TFLOP/s (10*B*H*S^2*D / t)", "value": round(flops / (wall_ms * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: SDPA bwd {'causal' if causal else 'non-causal'} B={w.B} H={w.H} S={w.S} D={w.D} {dtype}"},
+        "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(tf / PEAK_MFMA_TFLOPS, 4), "traffic": None,
+                     "kernel": "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<keys resident> + sdpa_bwd_kernel<queries resident>",
+                     "ms_avg_all_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
+                     "executed_mfma_flops_per_launch": flops * 7.0 / 5.0}}), flush=True)
+
+
 def cpu_baseline(w, q, k, v, target_seconds):
     """Time the unmodified float64 CPU checker on a bounded sample of the same workload."""
     from oracle import sdpa_oracle
@@ -269,6 +319,9 @@ def main():
 
     if args.kv:
         bench_kv(pkg, torch, args, tile, flags)
+        return
+    if args.bwd:
+        bench_bwd(pkg, torch, args, flags)
         return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape)

@@ -7,21 +7,20 @@
 
 namespace tsdpa {
 
-// Tile shapes (resident rows = 32*NW per workgroup, TS streamed rows per tile) and the wavefronts per
-// SIMD the register budget is sized for.  The keys-resident pass keeps two operand sets and two output
-// accumulators in registers: at D = 128 that needs more than 256 registers per lane, so one wavefront per SIMD.
+// Tile shapes, from timings on MI355X: 32*NW resident rows per workgroup, TS streamed rows per tile for
+// the dQ / dK / dV pass, and the wavefronts per SIMD the register budget is sized for.  At D = 128 the
+// dK pass (two resident operand sets, one output, per-row statistics) is the tightest on registers
+// and runs best on 32-row tiles.
 template <int D> struct BwdShape;
-template <> struct BwdShape<64>  { static constexpr int NW = 4, TS_Q = 64, WPS_Q = 2, TS_K = 64, WPS_K = 2; };
-template <> struct BwdShape<128> { static constexpr int NW = 4, TS_Q = 64, WPS_Q = 2, TS_K = 32, WPS_K = 1; };
+template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 64, 64}; };
+template <> struct BwdShape<128> { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 32, 64}; };
 
-template <typename T, int D, bool KEYS_RES>
+template <typename T, int D, int MODE>
 int launch_bwd_pass(const BwdLaunchArgs &a)
 {
     using Sh = BwdShape<D>;
-    constexpr int NW = Sh::NW;
-    constexpr int TS = KEYS_RES ? Sh::TS_K : Sh::TS_Q;
-    constexpr int WPS = KEYS_RES ? Sh::WPS_K : Sh::WPS_Q;
-    auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, KEYS_RES>;
+    constexpr int NW = Sh::NW, TS = Sh::TS[MODE], WPS = Sh::WPS;
+    auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, MODE>;
     constexpr int lds_bytes = BwdGeom<D, TS>::LDS_BYTES;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -31,10 +30,10 @@ int launch_bwd_pass(const BwdLaunchArgs &a)
     if (attr_err != hipSuccess) return (int)attr_err;
     const int nR = (a.S + NW * 32 - 1) / (NW * 32);
     const int N = a.BH * nR;
+    void *out = MODE == BWD_DQ ? a.dq : (MODE == BWD_DK ? a.dk : a.dv);
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
-                       (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.lse2, a.delta,
-                       (T *)(KEYS_RES ? a.dk : a.dq), (T *)(KEYS_RES ? a.dv : nullptr),
-                       a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes);
+                       (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.delta,
+                       (T *)out, a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes);
     return (int)hipGetLastError();
 }
 
@@ -47,9 +46,11 @@ int launch_bwd(const BwdLaunchArgs &a)
                        (const T *)a.o, (const T *)a.dout, a.lse, a.delta, a.lse2, rows);
     int err = (int)hipGetLastError();
     if (err != 0) return err;
-    err = launch_bwd_pass<T, D, true>(a);
+    err = launch_bwd_pass<T, D, BWD_DV>(a);
     if (err != 0) return err;
-    return launch_bwd_pass<T, D, false>(a);
+    err = launch_bwd_pass<T, D, BWD_DK>(a);
+    if (err != 0) return err;
+    return launch_bwd_pass<T, D, BWD_DQ>(a);
 }
 
 }  // namespace tsdpa

@@ -8,17 +8,19 @@
 //     dS_ij = P_ij (dP_ij - Delta_i),   Delta_i = <dO_i, O_i>   (= sum_j P_ij dP_ij)
 //     dQ_i  = scale * sum_j dS_ij k_j,  dK_j = scale * sum_i dS_ij q_i
 //
-// Two passes over the S x S score plane, both instances of ONE kernel template, so that no sum
-// crosses workgroups (no atomics, deterministic results):
-//   * QUERIES resident (KEYS_RES = false): a workgroup owns 32*NW query rows (Q and dO rows in
-//     registers), streams K and V tiles, produces dQ;
-//   * KEYS resident (KEYS_RES = true): a workgroup owns 32*NW key rows (K and V rows in registers),
-//     streams Q and dO tiles, produces dK and dV.
-// With R the resident and T the streamed rows, both passes compute, per streamed tile,
-//     acc[t][r]  = <T1_t, R1_r>  (scores)        acc2[t][r] = <T2_t, R2_r>  (dP)
-//     out1^T[d][r] += sum_t T1[t][d] dS[t][r]    (dQ^T or dK^T)
-//     out2^T[d][r] += sum_t T2[t][d] P[t][r]     (dV^T; keys-resident pass only)
-// (T1, T2, R1, R2) = (K, V, Q, dO) or (Q, dO, K, V).  The MFMA formulation is the forward kernel's:
+// Three passes over the S x S score plane, all instances of ONE kernel template, so that no sum
+// crosses workgroups (no atomics, deterministic results) and every pass fits 256 registers per lane
+// (two wavefronts per SIMD):
+//   * BWD_DQ: a workgroup owns 32*NW query rows (Q and dO rows in registers), streams K and V tiles;
+//   * BWD_DK: a workgroup owns 32*NW key rows (K and V rows in registers), streams Q and dO tiles;
+//   * BWD_DV: a workgroup owns 32*NW key rows (K rows in registers), streams Q and dO tiles.
+// With R the resident and T the streamed rows, a pass computes, per streamed tile,
+//     acc[t][r]  = <T1_t, R1_r>  (scores)        acc2[t][r] = <T2_t, R2_r>  (dP; not in BWD_DV)
+//     out^T[d][r] += sum_t T1[t][d] dS[t][r]     (dQ^T or dK^T)
+//     out^T[d][r] += sum_t T2[t][d] P[t][r]      (dV^T, BWD_DV)
+// (T1, T2, R1, R2) = (K, V, Q, dO) or (Q, dO, K, V).  The scores are thus computed three times and dP
+// twice (8 S x S x D products against the 5 of the formulas): the price of keeping dK and dV out of
+// one register file.  The MFMA formulation is the forward kernel's:
 // transposed accumulators (a lane owns one resident row), P and dS handed to the second product
 // straight from the accumulator registers as B-operands, the streamed tile read row-wise for the
 // first product and through the transposing LDS read for the second.  Since one LDS tile now serves
@@ -41,7 +43,8 @@ template <int D, int TS> struct BwdGeom {
     static constexpr int DG = D;
     static constexpr int ROW = DG * 2;
     static constexpr int TILE = TS * ROW;
-    static constexpr int LDS_BYTES = 4 * TILE;      // T1 slots 0,1 then T2 slots 0,1
+    static constexpr int STATS = 2 * TS * 4;        // LSE then Delta of a tile's rows (keys-resident passes)
+    static constexpr int LDS_BYTES = 4 * TILE + 2 * STATS;   // T1 slots 0,1, T2 slots 0,1, statistics slots 0,1
     static __host__ __device__ constexpr int swz(int r) {
         return DG == 64 ? ((((r >> 1) & 1) << 2) | ((r >> 2) & 3)) : (((r & 3) << 2) | ((r >> 2) & 3));
     }
@@ -80,11 +83,13 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 #endif
 }
 
-template <typename T, int D, int NW, int TS, int WPS, bool KEYS_RES>
+enum { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2 };
+
+template <typename T, int D, int NW, int TS, int WPS, int MODE>
 __global__ void __launch_bounds__(NW * 64, WPS)
 sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
-                const T *__restrict__ dout, const float *__restrict__ lse2, const float *__restrict__ delta,
-                T *__restrict__ out1, T *__restrict__ out2,   // dQ, unused  or  dK, dV
+                const T *__restrict__ dout, const float *__restrict__ stats,   // Delta [B*H*S + slack], then LSE likewise
+                T *__restrict__ out,   // dQ, dK or dV
                 int S, int nR, int N, float c, float scale, uint32_t rsign, int causal, unsigned stat_bytes)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -92,6 +97,8 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using vec8 = typename E::vec8;
     using vec4 = typename E::vec4;
     using G = BwdGeom<D, TS>;
+    constexpr bool KEYS_RES = MODE != BWD_DQ;
+    constexpr bool NEED_DP = MODE != BWD_DV;      // dP product and Delta
     constexpr int RM = NW * 32;                   // resident rows per workgroup
     constexpr int CPR = G::DG / 8;                // 16-byte chunks per row
     constexpr int NLD = TS * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
@@ -126,7 +133,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         u32x4 raw = *(const u32x4 *)(r1 + (size_t)rrow_c * D + kk * 16 + g * 8);
         raw ^= rsign;
         rf1[kk] = __builtin_bit_cast(vec8, raw);
-        rf2[kk] = *(const vec8 *)(r2 + (size_t)rrow_c * D + kk * 16 + g * 8);
+        if constexpr (NEED_DP) rf2[kk] = *(const vec8 *)(r2 + (size_t)rrow_c * D + kk * 16 + g * 8);
     }
 
     // ---- range of streamed tiles, and the streamed rows [tlo, thi] that pair with this lane's row
@@ -139,14 +146,20 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         else { j1 = last_row / TS + 1; thi = rrow < S ? rrow : S - 1; }   // keys up to the query
     }
 
-    // per-row statistics of the query side: LSE (log2 units) and Delta
-    // (the descriptors span the whole arrays, slack included: a 4-row read never straddles their end;
-    // rows >= S of a head pick up the next head's or the slack's values and are masked)
+    // per-row statistics of the query side, LSE (log2 units) and Delta: scalars of this lane's row, or
+    // (keys-resident pass) streamed into the LDS with each tile.  The descriptor spans both arrays,
+    // slack included; rows >= S of a head pick up the next head's or the slack's values and are masked.
+    const float *delta = stats, *lse2 = (const float *)((const char *)stats + stat_bytes);
     float lse_r = 0.f, delta_r = 0.f;
     if (!KEYS_RES) { lse_r = lse2[(size_t)head * S + rrow_c]; delta_r = delta[(size_t)head * S + rrow_c]; }
-    const auto lse_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)lse2, (short)0, (int)stat_bytes, 0x00020000);
-    const auto delta_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)delta, (short)0, (int)stat_bytes, 0x00020000);
-    const int stat_soff = head * S * 4;
+    const auto stat_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)stats, (short)0, (int)(2 * stat_bytes), 0x00020000);
+    constexpr int NST = 2 * TS / 64;              // 4-byte direct-to-LDS loads (wavefront 0) per tile: LSE rows, then Delta rows
+    int stat_goff[NST];
+#pragma unroll
+    for (int it = 0; it < NST; ++it) {
+        const int e = it * 64 + lane;             // element of the tile's statistics block
+        stat_goff[it] = (e / TS == 0 ? (int)stat_bytes : 0) + (head * S + e % TS) * 4;
+    }
 
     // ---- streamed tiles HBM -> LDS, as in the forward kernel: a descriptor per tensor covers this
     // head's S rows (rows >= S read as zeros), lane `lane` of load `it` fills LDS chunk
@@ -167,16 +180,25 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
                                                      goff[it], soff, 0, 0);
     };
-    constexpr int T1SLOT0 = 0, T1SLOT1 = G::TILE, T2SLOT0 = 2 * G::TILE, T2SLOT1 = 3 * G::TILE;
+    constexpr int T2BASE = 2 * G::TILE;           // T1 slot s at s*TILE, T2 slot s at T2BASE + s*TILE
+    constexpr int STBASE = 4 * G::TILE;           // statistics slot s at STBASE + s*STATS
+    auto stat_slot = [](int slot) { return STBASE + slot / G::TILE * G::STATS; };
+    auto load_stats = [&](int j, int slot) {
+        if constexpr (KEYS_RES) {
+            if (wave == 0) {
+#pragma unroll
+                for (int it = 0; it < NST; ++it)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(stat_rsrc, (TSDPA_LDS void *)(lds + stat_slot(slot) + it * 256), 4,
+                                                             stat_goff[it], j * TS * 4, 0, 0);
+            }
+        }
+    };
 
-    f32x16 o1[DB], o2[KEYS_RES ? DB : 1];
+    f32x16 oacc[DB];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            o1[db][i] = 0.f;
-            if constexpr (KEYS_RES) o2[db][i] = 0.f;
-        }
+        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
 
     // ---- per-lane LDS read offsets (tile slot, nb, ks enter as immediates)
     // row-wise: row l32 (+32*nb), chunk (2*kk + g) ^ swz(row)
@@ -221,49 +243,52 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 }
     };
 
-    vec8 xp[KEYS_RES ? NB : 1][2], xds[NB][2];
-
+    // One streamed tile: P (and dS) from the first products, rounded to 16 bits as B-operands of the
+    // second product.  The next tile's loads are issued first and land while this one is computed.
+    vec8 xb[NB][2];
     auto tile = [&](int j, auto par_tag, auto mask_tag) {
         constexpr int PAR = decltype(par_tag)::value;
         constexpr bool MASK = decltype(mask_tag)::value;
-        constexpr int s1 = PAR ? T1SLOT1 : T1SLOT0, s2 = PAR ? T2SLOT1 : T2SLOT0;
-        // statistics of the streamed query rows (keys-resident pass): 4 consecutive rows per load,
-        // issued before the next tile's loads so that waiting for them does not wait for those
-        f32x4 st_lse[KEYS_RES ? NB : 1][4], st_delta[KEYS_RES ? NB : 1][4];
-        if constexpr (KEYS_RES) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int off = (j * TS + nb * 32 + r4 * 8 + g * 4) * 4;
-                    st_lse[nb][r4] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(lse_rsrc, off, stat_soff, 0));
-                    st_delta[nb][r4] = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(delta_rsrc, off, stat_soff, 0));
-                }
-        }
-        load_tile(t1_rsrc, j + 1, lds + (PAR ? T1SLOT0 : T1SLOT1));
-        load_tile(t2_rsrc, j + 1, lds + (PAR ? T2SLOT0 : T2SLOT1));
+        constexpr int cur = PAR * G::TILE, nxt = (1 - PAR) * G::TILE;
+        load_stats(j + 1, nxt);
+        load_tile(t1_rsrc, j + 1, lds + nxt);
+        load_tile(t2_rsrc, j + 1, lds + T2BASE + nxt);
         const int trow0 = j * TS + g * 4;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {       // one 32-row block at a time: only its two accumulators are live
+        for (int nb = 0; nb < NB; ++nb) {       // one 32-row block at a time: only its accumulators are live
             f32x16 sacc, dpacc;
-            products(s1, nb, rf1, sacc);
-            products(s2, nb, rf2, dpacc);
+            products(cur, nb, rf1, sacc);
+            if constexpr (NEED_DP) products(T2BASE + cur, nb, rf2, dpacc);
+            // the 16 streamed rows this lane meets in the block come in 4 runs of 4 consecutive rows; in the
+            // keys-resident passes their statistics are read from the LDS run by run (the scheduling
+            // barriers keep the compiler from fetching all of them ahead, which costs 32 registers)
+            const lds_ptr sp = lds + stat_slot(cur) + (nb * 32 + g * 4) * 4;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float l2 = KEYS_RES ? st_lse[KEYS_RES ? nb : 0][i >> 2][i & 3] : lse_r;
-                const float dl = KEYS_RES ? st_delta[KEYS_RES ? nb : 0][i >> 2][i & 3] : delta_r;
-                float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], c, -l2));
-                float ds = p * (dpacc[i] - dl);
-                if constexpr (MASK) {
-                    const int trow = trow0 + nb * 32 + (i >> 2) * 8 + (i & 3);
-                    if (trow < tlo || trow > thi) { p = 0.f; ds = 0.f; }
+            for (int r4 = 0; r4 < 4; ++r4) {
+                f32x4 st_lse, st_delta;
+                if constexpr (KEYS_RES) {
+                    st_lse = *(TSDPA_LDS f32x4 *)(sp + r4 * 32);
+                    if constexpr (NEED_DP) st_delta = *(TSDPA_LDS f32x4 *)(sp + TS * 4 + r4 * 32);
                 }
-                xds[nb][i >> 3][i & 7] = (T)ds;
-                if constexpr (KEYS_RES) xp[nb][i >> 3][i & 7] = (T)p;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = r4 * 4 + e;
+                    const float l2 = KEYS_RES ? st_lse[e] : lse_r;
+                    float x = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], c, -l2));        // P
+                    if constexpr (NEED_DP) {
+                        const float dl = KEYS_RES ? st_delta[e] : delta_r;
+                        x *= dpacc[i] - dl;                                                   // dS
+                    }
+                    if constexpr (MASK) {
+                        const int trow = trow0 + nb * 32 + r4 * 8 + e;
+                        if (trow < tlo || trow > thi) x = 0.f;
+                    }
+                    xb[nb][i >> 3][i & 7] = (T)x;
+                }
+                if constexpr (KEYS_RES) __builtin_amdgcn_sched_barrier(0);
             }
         }
-        accumulate(s1, xds, o1);
-        if constexpr (KEYS_RES) accumulate(s2, xp, o2);
+        accumulate(MODE == BWD_DV ? T2BASE + cur : cur, xb, oacc);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
@@ -271,16 +296,16 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
     // a tile needs the masked path if it reaches past row S-1 or (causal) crosses the diagonal of any
-    // of this workgroup's rows; such tiles sit at the end of the range (queries resident) or at its
-    // start and, for the ragged tail, its end (keys resident).  Unmasked tiles run in pairs.
+    // of this workgroup's rows
     auto needs_mask = [&](int j) -> bool {
         if ((j + 1) * TS > S) return true;
         if (!causal) return false;
         return KEYS_RES ? j * TS < r0 + RM - 1 : (j + 1) * TS - 1 > r0;
     };
     if (j0 < j1) {
-        load_tile(t1_rsrc, j0, lds + T1SLOT0);
-        load_tile(t2_rsrc, j0, lds + T2SLOT0);
+        load_stats(j0, 0);
+        load_tile(t1_rsrc, j0, lds);
+        load_tile(t2_rsrc, j0, lds + T2BASE);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
         int j = j0;
@@ -299,8 +324,8 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     // ---- store: out^T tiles are turned through LDS (as the forward kernel's O) and written as whole
-    // rows; dQ and dK carry the factor `scale` of the score, dV none.  The last barrier of the loop
-    // has every wavefront past its last LDS read.
+    // rows; dQ and dK carry the factor `scale` of the score, dV none.  The last barrier of the loop has
+    // every wavefront past its last LDS read.
     auto store = [&](const f32x16 (&acc)[DB], float factor, T *dst) {
         constexpr int CMASK = CPR - 1;
         const lds_ptr ow = lds + wave * (32 * G::ROW);
@@ -324,8 +349,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         }
     };
     static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");
-    store(o1, scale, out1);
-    if constexpr (KEYS_RES) store(o2, 1.0f, out2);
+    store(oacc, MODE == BWD_DV ? 1.0f : scale, out);
 #endif
 }
 
