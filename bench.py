@@ -53,7 +53,7 @@ def parse_args():
                     help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
     ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
     ap.add_argument("--bwd", action="store_true",
-                    help="time the backward pass (tiled_sdpa_bwd: statistics, dK/dV and dQ kernels) of the workload")
+                    help="time the backward pass (tiled_sdpa_bwd: statistics, dV, dK and dQ kernels) of the workload")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
@@ -266,9 +266,9 @@ def bench_bwd(pkg, torch, args, flags):
         "config": {"workload": f"{w.name}: SDPA bwd {'causal' if causal else 'non-causal'} B={w.B} H={w.H} S={w.S} D={w.D} {dtype}"},
         "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf / PEAK_MFMA_TFLOPS, 4), "traffic": None,
-                     "kernel": "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<keys resident> + sdpa_bwd_kernel<queries resident>",
+                     "kernel": "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dV> + sdpa_bwd_kernel<dK> + sdpa_bwd_kernel<dQ>",
                      "ms_avg_all_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
-                     "executed_mfma_flops_per_launch": flops * 7.0 / 5.0}}), flush=True)
+                     "executed_mfma_flops_per_launch": flops * 8.0 / 5.0}}), flush=True)
 
 
 def cpu_baseline(w, q, k, v, target_seconds):
