@@ -1,4 +1,4 @@
-"""MI355X-native tiled SDPA forward (online softmax, streamed K/V tiles).
+"""MI355X-native tiled SDPA (online softmax, streamed K/V tiles): forward, split-KV / decoding shapes, backward.
 
 The compute path is the HIP library ``libtiled_sdpa.so`` built from ``csrc/``;
 :mod:`.binding` marshals torch tensors to its C-ABI.  :mod:`.workloads` only

@@ -1,4 +1,4 @@
-// C-ABI of the tiled SDPA forward library: argument validation, tile heuristic, dispatch.
+// C-ABI of the tiled SDPA library: argument validation, tile and split heuristics, dispatch.
 // See include/tiled_sdpa.h for the contract of every entry point.
 #include "tiled_sdpa.h"
 

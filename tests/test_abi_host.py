@@ -147,6 +147,35 @@ def test_kv_workspace_size_and_default_splits(lib):
         binding.kv_default_splits(1, 1, 8, 4, 64, binding.F16, binding.FLAG_CAUSAL)
 
 
+@pytest.mark.parametrize("kwargs,expect", [
+    (dict(dtype=3), DTYPE),
+    (dict(D=96), BAD_D),                           # the backward pass covers D = 64 and 128
+    (dict(D=160), BAD_D),
+    (dict(S=-1), SHAPE),
+    (dict(B=1 << 10, H=1 << 10, S=1 << 10), SHAPE),    # statistics arrays beyond a 32-bit byte range
+    (dict(S=0, q=None, dq=None, ws=None), OK),
+    (dict(dout=None), NULL),
+    (dict(lse=None), NULL),
+    (dict(dv=None), NULL),
+    (dict(dk=P + 8), ALIGN),
+    (dict(lse=P + 2), ALIGN),
+    (dict(scale=-math.inf), SCALE),
+    (dict(ws=None), WORKSPACE),
+    (dict(ws=P + 4), WORKSPACE),
+    (dict(ws_bytes=2 * (2 * 3 * 50 + 128) * 4 - 1), WORKSPACE),
+])
+def test_backward_entry_point_validation_order_and_codes(lib, kwargs, expect):
+    a = dict(q=P, k=P, v=P, o=P, dout=P, lse=P, dq=P, dk=P, dv=P, B=2, H=3, S=50, D=128, scale=0.125,
+             dtype=0, flags=0, ws=P, ws_bytes=1 << 20, stream=None)
+    a.update(kwargs)
+    st = binding.tiled_sdpa_bwd(a["q"], a["k"], a["v"], a["o"], a["dout"], a["lse"], a["dq"], a["dk"], a["dv"],
+                                a["B"], a["H"], a["S"], a["D"], a["scale"], a["dtype"], a["flags"],
+                                a["ws"], a["ws_bytes"], a["stream"])
+    assert st == expect, binding.status_string(st)
+    assert binding.bwd_workspace_bytes(2, 3, 50) == 2 * (2 * 3 * 50 + 128) * 4
+    assert binding.bwd_workspace_bytes(-1, 3, 50) == 0
+
+
 def test_probe_validates_before_touching_the_gpu(lib):
     import ctypes
     fl = ctypes.c_double(-1.0)
