@@ -173,7 +173,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         const int r = p / CPR, cp = p % CPR;
         goff[it] = r * G::ROW + ((cp ^ G::swz(r)) << 4);
     }
-    auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) {
+    auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) __attribute__((always_inline)) {
         const int soff = (j < j1 ? j : nT) * G::TILE;     // a tile past the range: outside the descriptor, zeros
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
@@ -183,7 +183,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     constexpr int T2BASE = 2 * G::TILE;           // T1 slot s at s*TILE, T2 slot s at T2BASE + s*TILE
     constexpr int STBASE = 4 * G::TILE;           // statistics slot s at STBASE + s*STATS
     auto stat_slot = [](int slot) { return STBASE + slot / G::TILE * G::STATS; };
-    auto load_stats = [&](int j, int slot) {
+    auto load_stats = [&](int j, int slot) __attribute__((always_inline)) {
         if constexpr (KEYS_RES) {
             if (wave == 0) {
 #pragma unroll
@@ -217,7 +217,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     // acc[i] = <T_row, R_col>, row = nb*32 + (i/4)*8 + g*4 + i%4 of the tile, col = this lane's row
-    auto products = [&](int slot, int nb, const vec8 (&rf)[KK], f32x16 &acc) {
+    auto products = [&](int slot, int nb, const vec8 (&rf)[KK], f32x16 &acc) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
@@ -228,7 +228,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     // out^T += T^T X, X taken from accumulator layout as B-operands (k-slots 0..3 / 4..7 of a lane <->
     // tile rows base+g*4+0..3 / base+8+g*4+0..3, mirrored on the A side by the two transposing reads)
-    auto accumulate = [&](int slot, const vec8 (&xb)[NB][2], f32x16 (&out)[DB]) {
+    auto accumulate = [&](int slot, const vec8 (&xb)[NB][2], f32x16 (&out)[DB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -246,7 +246,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // One streamed tile: P (and dS) from the first products, rounded to 16 bits as B-operands of the
     // second product.  The next tile's loads are issued first and land while this one is computed.
     vec8 xb[NB][2];
-    auto tile = [&](int j, auto par_tag, auto mask_tag) {
+    auto tile = [&](int j, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int cur = PAR * G::TILE, nxt = (1 - PAR) * G::TILE;
@@ -297,7 +297,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using P1 = std::integral_constant<int, 1>;
     // a tile needs the masked path if it reaches past row S-1 or (causal) crosses the diagonal of any
     // of this workgroup's rows
-    auto needs_mask = [&](int j) -> bool {
+    auto needs_mask = [&](int j) __attribute__((always_inline)) -> bool {
         if ((j + 1) * TS > S) return true;
         if (!causal) return false;
         return KEYS_RES ? j * TS < r0 + RM - 1 : (j + 1) * TS - 1 > r0;
@@ -326,7 +326,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // ---- store: out^T tiles are turned through LDS (as the forward kernel's O) and written as whole
     // rows; dQ and dK carry the factor `scale` of the score, dV none.  The last barrier of the loop has
     // every wavefront past its last LDS read.
-    auto store = [&](const f32x16 (&acc)[DB], float factor, T *dst) {
+    auto store = [&](const f32x16 (&acc)[DB], float factor, T *dst) __attribute__((always_inline)) {
         constexpr int CMASK = CPR - 1;
         const lds_ptr ow = lds + wave * (32 * G::ROW);
 #pragma unroll

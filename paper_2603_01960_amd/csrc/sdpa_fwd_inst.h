@@ -12,11 +12,11 @@ namespace tsdpa {
 
 constexpr int kLdsPerCU = 160 * 1024;
 
-template <int D, int NW, int TN> constexpr int waves_per_simd() {
-    int wgs = kLdsPerCU / TileGeom<D, TN>::LDS_BYTES;
-    int w = wgs * NW / 4;
-    return w < 1 ? 1 : (w > 2 ? 2 : w);
-}
+// Register budget of every instantiation: two wavefronts per SIMD, i.e. 256 registers per lane, also
+// where the LDS admits only one.  A budget of one wavefront per SIMD (512 registers) makes the
+// compiler split accumulators between the VGPR and AGPR halves and move them back and forth (or to
+// scratch) inside the loop; with 256 every tile shape here compiles without spills.
+template <int D, int NW, int TN> constexpr int waves_per_simd() { return 2; }
 
 template <typename T, int D, int NW, int TN, bool KV = false>
 int launch_one(const LaunchArgs &a)

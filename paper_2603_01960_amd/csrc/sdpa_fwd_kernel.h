@@ -10,8 +10,6 @@
 //     16 B contiguously, so rows cannot be padded; bank conflicts are avoided by an XOR swizzle of
 //     the 16-byte chunks within each row, applied through the choice of the global address each
 //     lane fetches.  Rows past S are never fetched: the buffer descriptor's range check returns 0;
-//   * K runs one tile ahead of V so the scores of tile j+1 (matrix pipe) overlap the softmax of
-//     tile j (vector ALU) inside every wavefront;
 //   * scores are computed TRANSPOSED, S^T = K Q^T, with v_mfma_f32_32x32x16: in the 32x32
 //     accumulator layout a lane then owns ONE query column and 16 of the 32 key rows, so the row
 //     maximum / sum of Eqs. 2-3 are in-lane reductions plus one exchange with lane^32, and m, l and
@@ -206,7 +204,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
         v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
     }
-    auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) {
+    auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) __attribute__((always_inline)) {
         // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
         // outside the descriptor and read as zeros without a memory access, and so does a tile this
@@ -245,7 +243,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         v_roff[db] = v_row * G::ROW + ((db ^ G::vswz(v_row)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
 
     // scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
-    auto scores = [&](int kslot, f32x16 (&sacc)[NB]) {
+    auto scores = [&](int kslot, f32x16 (&sacc)[NB]) __attribute__((always_inline)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -262,7 +260,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // Eq. 2 on one tile of scores: tile maximum, reference update and (rarely) the rescale of Eqs. 3-4.
     // Kept apart from the exponentials because it ends in a branch: everything after it (scores of the
     // next tile, exponentials, PV product) then forms one straight-line block the scheduler can interleave.
-    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto mask_tag) {
+    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto mask_tag) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
         if constexpr (MASK) {
@@ -294,7 +292,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p,
     // left in pb as MFMA B-operands
-    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) {
+    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
         float psum[4] = {0.f, 0.f, 0.f, 0.f};
@@ -313,7 +311,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
 
     // Eq. 4: O^T += V^T P^T
-    auto accumulate = [&](int vslot, const vec8 (&pb)[NB][2]) {
+    auto accumulate = [&](int vslot, const vec8 (&pb)[NB][2]) __attribute__((always_inline)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -329,58 +327,49 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 }
     };
 
-    // ---- software pipeline, unrolled by two so that LDS slots and score registers alternate by name.
-    // K runs one tile ahead of V: while the VALU does the softmax of tile j, the matrix pipe already
-    // computes the scores of tile j+1.  In step j the LDS holds K(j+1) and V(j); K(j+2) and V(j+1) are
-    // in flight into the slots that K(j) and V(j-1) occupied, whose last readers finished before the
-    // barrier that ended step j-1.
-    f32x16 s_a[NB], s_b[NB];
+    // ---- main loop, unrolled by two so that the LDS slots alternate by name.  In step j the LDS holds
+    // K(j) and V(j); K(j+1) and V(j+1) are in flight into the other slots, whose last readers finished
+    // before the barrier that ended step j-1.  Overlap of matrix and vector work comes from the two
+    // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
+    // ahead cost 32 registers and measured 4 % slower).
+    f32x16 sacc[NB];
     vec8 pb[NB][2];
     if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
     load_tile(k_rsrc, k_goff, t0, lds + KSLOT0);
     load_tile(v_rsrc, v_goff, t0, lds + VSLOT0);
-    load_tile(k_rsrc, k_goff, t0 + 1, lds + KSLOT1);   // past the end of a one-tile run: zeros, never used
     TSDPA_WAIT_VMCNT0();
     __syncthreads();
-    scores(KSLOT0, s_a);
-    __syncthreads();   // step 0 overwrites K slot 0: every wavefront must have read it first
 
-    // step with tile j's scores in `cur`: PAR = (j - t0) & 1 selects the slots, MASK the masked code path
-    auto step = [&](int j, f32x16 (&cur)[NB], f32x16 (&nxt)[NB], auto par_tag, auto mask_tag) {
+    // tile j: PAR = (j - t0) & 1 selects the slots, MASK the masked code path
+    auto step = [&](int j, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
-        load_tile(k_rsrc, k_goff, j + 2, lds + (PAR ? KSLOT1 : KSLOT0));
-        load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
-        row_max(cur, j, mask_tag);
-        scores(PAR ? KSLOT0 : KSLOT1, nxt);
-        exponentials(cur, j, pb, mask_tag);
+        if (j + 1 < t1) {
+            load_tile(k_rsrc, k_goff, j + 1, lds + (PAR ? KSLOT0 : KSLOT1));
+            load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
+        }
+        scores(PAR ? KSLOT1 : KSLOT0, sacc);
+        row_max(sacc, j, mask_tag);
+        exponentials(sacc, j, pb, mask_tag);
         accumulate(PAR ? VSLOT1 : VSLOT0, pb);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
-    };
-    auto last = [&](int j, f32x16 (&cur)[NB], int vslot) {
-        row_max(cur, j, std::true_type{});
-        exponentials(cur, j, pb, std::true_type{});
-        accumulate(vslot, pb);
     };
     using P0 = std::integral_constant<int, 0>;
     using P1 = std::integral_constant<int, 1>;
     // tiles below nfull need no mask: they run in pairs through the unmasked step; the few tiles
     // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
     // masked path, which is also correct for a tile that turns out to need no mask
-    const int last_j = t1 - 1;                                // steps t0 .. last_j-1 have a next tile
-    const int fast_n = (last_j < nfull ? last_j : nfull) - t0;
+    const int fast_n = (t1 < nfull ? t1 : nfull) - t0;
     const int fast_end = t0 + (fast_n > 0 ? fast_n & ~1 : 0);
     int j = t0;
     for (; j < fast_end; j += 2) {
-        step(j, s_a, s_b, P0{}, std::false_type{});
-        step(j + 1, s_b, s_a, P1{}, std::false_type{});
+        step(j, P0{}, std::false_type{});
+        step(j + 1, P1{}, std::false_type{});
     }
-    for (; j < last_j; ++j) {
-        if ((j - t0) & 1) step(j, s_b, s_a, P1{}, std::true_type{});
-        else              step(j, s_a, s_b, P0{}, std::true_type{});
+    for (; j < t1; ++j) {
+        if ((j - t0) & 1) step(j, P1{}, std::true_type{});
+        else              step(j, P0{}, std::true_type{});
     }
-    if ((j - t0) & 1) last(j, s_b, VSLOT1);
-    else              last(j, s_a, VSLOT0);
     }
 
     // ---- O_i = o_i / l_i (Section 4.1.2), rounded once to the 16-bit output type.  The accumulators
@@ -416,7 +405,6 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     if (lse != nullptr && g == 0 && qrow < S)
         lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");
-    __syncthreads();   // all wavefronts are done reading the last V tile
     {
         constexpr int CMASK = CPR - 1;                // chunks per row is 8 or 16
         const lds_ptr ow = lds + wave * (32 * G::ROW);
