@@ -27,10 +27,10 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
 # scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", "bf16"): 680.9e6,   # 546.7 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
-    ("C5", "f16"): 626.6e6,    # 559.5 MB + 67.1 MB          (profiles/sdpa_fwd_C5_f16.md)
+    ("C4", "bf16"): 736.5e6,   # 602.2 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
+    ("C5", "f16"): 625.4e6,    # 558.3 MB + 67.1 MB          (profiles/sdpa_fwd_C5_f16.md)
     ("C3", "bf16"): 77.6e6,    # 58.2 MB + 19.4 MB           (profiles/sdpa_fwd_C3_bf16.md)
-    ("C2", "f16"): 33.7e6,     # 25.4 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
+    ("C2", "f16"): 33.7e6,     # 25.3 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
 }
 
 # The paper's own figures, other hardware (NVIDIA DGX GB10): context only, never a target.
