@@ -55,6 +55,8 @@ def parse_args():
     ap.add_argument("--bwd", action="store_true",
                     help="time the backward pass (tiled_sdpa_bwd: statistics, dV, dK and dQ kernels) of the workload")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
+    ap.add_argument("--qk-std", type=float, default=None,
+                    help="standard deviation of the Q and K entries (default: the workload's own; C5 uses sqrt(2))")
     ap.add_argument("--linear-grid", action="store_true", help="disable the per-XCD workgroup regrouping")
     ap.add_argument("--exact-max", action="store_true", help="raise the softmax reference on every new maximum")
     ap.add_argument("--causal", action="store_true",
@@ -72,13 +74,17 @@ def parse_args():
     return ap.parse_args()
 
 
-def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal", shape=None):
-    from paper_2603_01960_amd.workloads import Workload, make_qkv, make_workload
+def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal", shape=None, qk_std=None):
+    import dataclasses
+    from paper_2603_01960_amd.workloads import WORKLOADS, Workload, make_qkv, make_workload
     if shape is not None:
         B, H, S, D = shape
         dtype = dtype or "bf16"
         w = Workload(f"custom", B, H, S, D, (dtype,), 4242)
         q, k, v = make_qkv(B, H, S, D, dtype, w.seed)
+    elif qk_std is not None:
+        w = dataclasses.replace(WORKLOADS[name], qk_std=float(qk_std))
+        q, k, v = make_qkv(w.B, w.H, w.S, w.D, dtype or w.dtypes[0], w.seed, w.qk_std, w.v_std)
     else:
         w, q, k, v = make_workload(name, dtype)
     dtype = dtype or w.dtypes[0]
@@ -324,7 +330,7 @@ def main():
         bench_bwd(pkg, torch, args, flags)
         return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
-    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape)
+    r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape, args.qk_std)
     w, dtype = r["workload"], r["dtype"]
     flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
     tflops = flops / (r["ms_per_step"] * 1e-3) / 1e12

@@ -51,9 +51,11 @@ enum { TSDPA_MAX_SPLITS = 128 };
 enum {
     TSDPA_FLAG_LINEAR_GRID = 1u, /* workgroup i handles tile i (no per-XCD regrouping); for measurements */
     TSDPA_FLAG_EXACT_MAX = 2u,   /* raise the softmax reference m on every new row maximum (Eq. 2 literally).
-                                    Default: raise it only when the tile maximum exceeds it by more than
-                                    2^8, which gives the same O and lse up to rounding and skips most
-                                    rescales of the accumulator. */
+                                    Default: the weights of a tile are taken against the current reference
+                                    first, and it is raised (to the tile maximum, with the rescale of
+                                    Eqs. 3-4) only when their sum exceeds 2^8; this gives the same O and lse
+                                    up to rounding and spares most tiles the maximum and the rescale.  With
+                                    the flag most tiles are computed twice: for checking, not for speed. */
     TSDPA_FLAG_CAUSAL = 8u       /* causal mask (Section 4.1.3; Eq. 1 with M_ij = -inf for j > i): key j
                                     contributes to query row i only if j <= i.  K/V tiles strictly above
                                     the diagonal of a workgroup's rows are neither read nor computed. */

@@ -223,10 +223,17 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
     // Online-softmax state (Eqs. 2-4), all in the log2 domain of s*c.  m_ref is the reference the
-    // exponentials are taken against: it is raised to the tile maximum only when that exceeds it by
-    // more than tau (tau = 0 is Eq. 2 literally).  With a stale reference the weights are merely
-    // scaled by a common factor <= 2^tau per row, which cancels in o/l and in m_ref + log2(l).
+    // exponentials are taken against.  It is not the running maximum of Eq. 2 but a stale one: a tile's
+    // weights p = 2^(s*c - m_ref) are computed first, and only if this lane's sum of them exceeds
+    // 2^tau (some score lies far above the reference; always so on a row's first tile, where m_ref is
+    // -inf) is the tile maximum taken, the reference raised to it, the state rescaled (Eqs. 3-4) and
+    // the weights recomputed.  With a stale reference the weights of a row are merely scaled by a common
+    // factor <= 2^tau, which cancels in o/l and in m_ref + log2(l); in return the common case needs
+    // neither the maximum nor the rescale.  tau = 0 raises the reference on every new maximum (any
+    // weight above 1 makes the sum exceed 1), which is Eq. 2 literally, at the price of recomputing
+    // most tiles.
     float m_ref = -INFINITY;
+    const float lazy_limit = __builtin_amdgcn_exp2f(tau);
     float l_run = 0.f;         // this lane's share of the normaliser (lane^32 holds the rest)
 
     // ---- per-lane LDS read addresses (loop invariant; tile slot, nb, ks enter as immediates)
@@ -257,10 +264,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             }
     };
 
-    // Eq. 2 on one tile of scores: tile maximum, reference update and (rarely) the rescale of Eqs. 3-4.
-    // Kept apart from the exponentials because it ends in a branch: everything after it (scores of the
-    // next tile, exponentials, PV product) then forms one straight-line block the scheduler can interleave.
-    auto row_max = [&](f32x16 (&sacc)[NB], int j, auto mask_tag) __attribute__((always_inline)) {
+    // Eq. 2 on one tile of scores, for the rows whose weights overflowed the limit (`over`; the two lanes
+    // that share a row decide together): tile maximum, new reference and the rescale of Eqs. 3-4.
+    auto raise_reference = [&](f32x16 (&sacc)[NB], int j, auto mask_tag, bool over) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
         if constexpr (MASK) {
@@ -277,21 +283,20 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[nb][i]);
         mx = pair_max(mx);
         const float m_tile = mx * c;
-        // always true on the first tile (m_ref = -inf); false for a row with every key of the tile masked
-        const bool grow = m_tile > m_ref + tau;
-        if (__builtin_amdgcn_ballot_w64(grow) != 0) {  // wavefront-uniform: rescale only when some row needs it
-            // rows that keep m_ref are left alone (also one whose keys so far were all masked: m_ref = -inf)
-            const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_tile) : 1.0f;
-            m_ref = grow ? m_tile : m_ref;
-            l_run *= alpha;
+        const bool row_over = pair_max(over ? 1.f : 0.f) > 0.f;
+        // rows that keep m_ref are left alone (also one whose keys so far were all masked: m_ref = -inf,
+        // m_tile = -inf or NaN)
+        const bool grow = row_over && m_tile > m_ref;
+        const float alpha = grow ? __builtin_amdgcn_exp2f(m_ref - m_tile) : 1.0f;
+        m_ref = grow ? m_tile : m_ref;
+        l_run *= alpha;
 #pragma unroll
-            for (int db = 0; db < DB; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-        }
+            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
     };
-    // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p, the PV product uses the 16-bit rounded p,
-    // left in pb as MFMA B-operands
+    // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p (this lane's share of the tile is returned),
+    // the PV product uses the 16-bit rounded p, left in pb as MFMA B-operands
     auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
@@ -307,7 +312,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 psum[i & 3] += p;
                 pb[nb][i >> 3][i & 7] = (T)p;
             }
-        l_run += (psum[0] + psum[1]) + (psum[2] + psum[3]);
+        return (psum[0] + psum[1]) + (psum[2] + psum[3]);
     };
 
     // Eq. 4: O^T += V^T P^T
@@ -348,8 +353,13 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
         }
         scores(PAR ? KSLOT1 : KSLOT0, sacc);
-        row_max(sacc, j, mask_tag);
-        exponentials(sacc, j, pb, mask_tag);
+        float ps = exponentials(sacc, j, pb, mask_tag);
+        const bool over = !(ps <= lazy_limit);               // also catches inf (first tile) and NaN
+        if (__builtin_amdgcn_ballot_w64(over) != 0) {        // wavefront-uniform and rare
+            raise_reference(sacc, j, mask_tag, over);
+            ps = exponentials(sacc, j, pb, mask_tag);
+        }
+        l_run += ps;
         accumulate(PAR ? VSLOT1 : VSLOT0, pb);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
