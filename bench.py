@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
 # scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", "bf16"): 736.5e6,   # 602.2 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
-    ("C5", "f16"): 625.4e6,    # 558.3 MB + 67.1 MB          (profiles/sdpa_fwd_C5_f16.md)
+    ("C4", "bf16"): 784.4e6,   # 625.0 MB fetched + 159.4 MB written (profiles/sdpa_fwd_C4_bf16.md)
+    ("C5", "f16"): 607.5e6,    # 527.8 MB + 79.7 MB          (profiles/sdpa_fwd_C5_f16.md)
     ("C3", "bf16"): 77.6e6,    # 58.2 MB + 19.4 MB           (profiles/sdpa_fwd_C3_bf16.md)
     ("C2", "f16"): 33.7e6,     # 25.3 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
 }
@@ -335,7 +335,7 @@ def main():
     flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
     tflops = flops / (r["ms_per_step"] * 1e-3) / 1e12
     kern_tflops = flops / (r["kernel_ms_avg"] * 1e-3) / 1e12
-    tm, tn = tile if tile else pkg.binding.default_tile(w.B, w.H, w.S, w.D, pkg.F16 if dtype == "f16" else pkg.BF16)
+    tm, tn = tile if tile else pkg.binding.default_tile(w.B, w.H, w.S, w.D, pkg.F16 if dtype == "f16" else pkg.BF16, flags)
 
     # which roof bounds the kernel: arithmetic intensity on compulsory bytes vs the ridge point
     comp_bytes = w.compulsory_bytes(2)

@@ -92,8 +92,9 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
                       int B, int H, int S, int D, float scale, int dtype, void *stream,
                       int tile_m, int tile_n, unsigned flags);
 
-/* The (tile_m, tile_n) the heuristic picks for a shape; returns a status code. */
-int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, int *tile_m, int *tile_n);
+/* The (tile_m, tile_n) the heuristic picks for a shape and flags (only TSDPA_FLAG_CAUSAL matters);
+ * returns a status code. */
+int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flags, int *tile_m, int *tile_n);
 
 /*
  * Forward pass for Sq query rows against Skv key/value rows, with the key range optionally split

@@ -60,7 +60,7 @@ def load_library():
     lib.tiled_sdpa_fwd_ex.restype = ci
     lib.tiled_sdpa_fwd_ex.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint]
     lib.tiled_sdpa_default_tile.restype = ci
-    lib.tiled_sdpa_default_tile.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ci), ctypes.POINTER(ci)]
+    lib.tiled_sdpa_default_tile.argtypes = [ci, ci, ci, ci, ci, ctypes.c_uint, ctypes.POINTER(ci), ctypes.POINTER(ci)]
     lib.tiled_sdpa_fwd_kv.restype = ci
     lib.tiled_sdpa_fwd_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, cf, ci, vp, ci, ci, ctypes.c_uint,
                                       ci, vp, ctypes.c_ulonglong]
@@ -90,9 +90,9 @@ def status_string(status: int) -> str:
     return load_library().tiled_sdpa_status_string(int(status)).decode()
 
 
-def default_tile(B: int, H: int, S: int, D: int, dtype: int):
+def default_tile(B: int, H: int, S: int, D: int, dtype: int, flags: int = 0):
     tm, tn = ctypes.c_int(0), ctypes.c_int(0)
-    st = load_library().tiled_sdpa_default_tile(B, H, S, D, dtype, ctypes.byref(tm), ctypes.byref(tn))
+    st = load_library().tiled_sdpa_default_tile(B, H, S, D, dtype, flags, ctypes.byref(tm), ctypes.byref(tn))
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return tm.value, tn.value

@@ -12,11 +12,13 @@ namespace tsdpa {
 
 constexpr int kLdsPerCU = 160 * 1024;
 
-// Register budget of every instantiation: two wavefronts per SIMD, i.e. 256 registers per lane, also
-// where the LDS admits only one.  A budget of one wavefront per SIMD (512 registers) makes the
-// compiler split accumulators between the VGPR and AGPR halves and move them back and forth (or to
-// scratch) inside the loop; with 256 every tile shape here compiles without spills.
-template <int D, int NW, int TN> constexpr int waves_per_simd() { return 2; }
+// Register budget of an instantiation, in wavefronts per SIMD (512 registers per lane divided among
+// them).  Three for 32-row K/V tiles up to D = 128: the main loop then fits 168 registers without
+// spilling and the third wavefront fills more of the phases in which the other two leave the matrix
+// pipe idle (+4-6 % on the long workloads).  Two otherwise, also where the LDS admits only one: a
+// budget of one wavefront per SIMD makes the compiler split accumulators between the VGPR and AGPR
+// halves and move them back and forth (or to scratch) inside the loop.
+template <int D, int NW, int TN> constexpr int waves_per_simd() { return (TN == 32 && D <= 128) ? 3 : 2; }
 
 template <typename T, int D, int NW, int TN, bool KV = false>
 int launch_one(const LaunchArgs &a)

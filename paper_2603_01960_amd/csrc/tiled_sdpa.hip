@@ -20,15 +20,19 @@ bool valid_tile(int tm, int tn, int D)
 }
 
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
-void pick_tile(int BH, int S, int D, int *tm, int *tn)
+void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
 {
     (void)BH;
-        // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts, two workgroups per
-    // CU) wins at every configuration measured; 64-row K/V tiles for long sequences, 32-row tiles when
-    // there are only a few tiles per head, so the pipeline fills sooner and the ragged tail wastes less.
+    // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts) win at every
+    // configuration measured.  K/V tiles: 32 rows when there are only a few tiles per head (the loop
+    // fills sooner, the ragged tail wastes less), 64 rows from S = 512 at D = 64.  At D = 96 and 128 the
+    // 32-row tile is the one that fits three wavefronts per SIMD and is 1-4 % ahead on long sequences,
+    // except under the causal mask, where its finer diagonal does not pay for the extra barriers.
+    // At D = 160 only the 32-row tile leaves room for two workgroups per CU (512-byte LDS rows).
     *tm = 128;
     *tn = S >= 512 ? 64 : 32;
-    if (D == 160) *tn = 32;       // 512-byte LDS rows: keeps two workgroups per CU
+    if (D == 160 || D == 96) *tn = 32;
+    if (D == 128 && !causal && S >= 1024) *tn = 32;
     if (S <= 64) *tm = 64;
 }
 
@@ -87,7 +91,7 @@ int validate_shape_kv(int B, int H, int Sq, int Skv, int D, int dtype, unsigned 
 void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 {
     *tm = Sq <= 64 ? 64 : 128;
-    *tn = (Skv >= 512 && D != 160) ? 64 : 32;
+    *tn = (Skv >= 512 && D != 160 && D != 96) ? 64 : 32;
 }
 
 }  // namespace
@@ -114,12 +118,12 @@ const char *tiled_sdpa_status_string(int status)
     }
 }
 
-int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, int *tile_m, int *tile_n)
+int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flags, int *tile_m, int *tile_n)
 {
     if (!tile_m || !tile_n) return TSDPA_ERR_NULL_PTR;
     const int st = validate_shape(B, H, S, D, dtype);
     if (st != TSDPA_OK) return st;
-    pick_tile(B * H, S, D, tile_m, tile_n);
+    pick_tile(B * H, S, D, (flags & TSDPA_FLAG_CAUSAL) != 0, tile_m, tile_n);
     return TSDPA_OK;
 }
 
@@ -134,7 +138,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o;
     if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     if (tile_m == 0 && tile_n == 0)
-        pick_tile(B * H, S, D, &tile_m, &tile_n);
+        pick_tile(B * H, S, D, (flags & TSDPA_FLAG_CAUSAL) != 0, &tile_m, &tile_n);
     else if (!valid_tile(tile_m, tile_n, D))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
