@@ -200,20 +200,27 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
         for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
 
-    // ---- per-lane LDS read offsets (tile slot, nb, ks enter as immediates)
+    // ---- per-lane LDS read pointers (tile slot, nb, ks enter as immediate offsets)
     // row-wise: row l32 (+32*nb), chunk (2*kk + g) ^ swz(row)
-    int row_off[KK];
+    lds_ptr row_ptr[KK];
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) row_off[kk] = l32 * G::ROW + (((2 * kk + g) ^ G::swz(l32)) << 4);
+    for (int kk = 0; kk < KK; ++kk) {
+        row_ptr[kk] = lds + l32 * G::ROW + (((2 * kk + g) ^ G::swz(l32)) << 4);
+        TSDPA_OPAQUE(row_ptr[kk]);
+    }
     // transposing: row g*4 + (lane%16)/4 (+ multiples of 8), bytes db*64 + ((lane/16)%2)*32 + (lane%4)*8
     // of the row, i.e. chunk db*4 + ((lane/16)%2)*2 + (lane%4)/2, swizzled.  Adding 8 to the row flips
     // bit 1 of swz (bit 5 of the byte offset); adding 16 or 32 leaves swz alone.
     const int t_row = g * 4 + ((lane & 15) >> 2);
-    int tr_off[DB];
+    lds_ptr tr_lo[DB], tr_hi[DB];                 // rows t_row (+16k) and t_row + 8 (+16k)
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
         const int chunk = db * 4 + ((lane >> 4) & 1) * 2 + ((lane & 3) >> 1);
-        tr_off[db] = t_row * G::ROW + ((chunk ^ G::swz(t_row)) << 4) + (lane & 1) * 8;
+        const int off = t_row * G::ROW + ((chunk ^ G::swz(t_row)) << 4) + (lane & 1) * 8;
+        tr_lo[db] = lds + off;
+        tr_hi[db] = lds + 8 * G::ROW + (off ^ 32);
+        TSDPA_OPAQUE(tr_lo[db]);
+        TSDPA_OPAQUE(tr_hi[db]);
     }
 
     // acc[i] = <T_row, R_col>, row = nb*32 + (i/4)*8 + g*4 + i%4 of the tile, col = this lane's row
@@ -222,7 +229,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            u32x4 raw = lds_read128(lds + slot + nb * 32 * G::ROW + row_off[kk]);
+            u32x4 raw = lds_read128(row_ptr[kk] + slot + nb * 32 * G::ROW);
             acc = E::mfma(__builtin_bit_cast(vec8, raw), rf[kk], acc);
         }
     };
@@ -235,9 +242,9 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
-                    const lds_ptr p0 = lds + slot + (nb * 32 + ks * 16) * G::ROW;
-                    i16x4 lo = lds_read_tr16(p0 + tr_off[db]);
-                    i16x4 hi = lds_read_tr16(p0 + 8 * G::ROW + (tr_off[db] ^ 32));
+                    const int tile_off = slot + (nb * 32 + ks * 16) * G::ROW;
+                    i16x4 lo = lds_read_tr16(tr_lo[db] + tile_off);
+                    i16x4 hi = lds_read_tr16(tr_hi[db] + tile_off);
                     i16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     out[db] = E::mfma(__builtin_bit_cast(vec8, a), xb[nb][ks], out[db]);
                 }

@@ -112,6 +112,11 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
     return x * base + (x < rem ? x : rem) + y;
 }
 
+// Hides how a register value was computed from the optimiser.  Used on loop-invariant LDS pointers:
+// left transparent, the compiler splits them into a common base and per-pointer offsets and re-adds the
+// two in front of every LDS read of the loop (one vector-ALU instruction per read).
+#define TSDPA_OPAQUE(x) asm volatile("" : "+v"(x))
+
 // s_waitcnt vmcnt(0) with the other counters left at their maxima (gfx9 encoding)
 #define TSDPA_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0F70)
 
@@ -236,18 +241,23 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const float lazy_limit = __builtin_amdgcn_exp2f(tau);
     float l_run = 0.f;         // this lane's share of the normaliser (lane^32 holds the rest)
 
-    // ---- per-lane LDS read addresses (loop invariant; tile slot, nb, ks enter as immediates)
+    // ---- per-lane LDS read pointers (loop invariant; tile slot, nb, ks enter as immediate offsets)
     // K: row l32 (+32*nb), chunk (2*kk + g) ^ kswz(row)
-    int k_roff[KK];
+    lds_ptr k_rptr[KK];
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk) k_roff[kk] = l32 * G::ROW + (((2 * kk + g) ^ G::kswz(l32)) << 4);
+    for (int kk = 0; kk < KK; ++kk) {
+        k_rptr[kk] = lds + l32 * G::ROW + (((2 * kk + g) ^ G::kswz(l32)) << 4);
+        TSDPA_OPAQUE(k_rptr[kk]);
+    }
     // V (transposing read): row g*4 + (lane%16)/4 (+ multiples of 8), 64-byte block db ^ vswz(row),
     // then 32 B for the upper 16 lanes of each 32 and 8 B per lane%4
     const int v_row = g * 4 + ((lane & 15) >> 2);
-    int v_roff[DB];
+    lds_ptr v_rptr[DB];
 #pragma unroll
-    for (int db = 0; db < DB; ++db)
-        v_roff[db] = v_row * G::ROW + ((db ^ G::vswz(v_row)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+    for (int db = 0; db < DB; ++db) {
+        v_rptr[db] = lds + v_row * G::ROW + ((db ^ G::vswz(v_row)) << 6) + ((lane >> 4) & 1) * 32 + (lane & 3) * 8;
+        TSDPA_OPAQUE(v_rptr[db]);
+    }
 
     // scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
     auto scores = [&](int kslot, f32x16 (&sacc)[NB]) __attribute__((always_inline)) {
@@ -259,7 +269,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         for (int kk = 0; kk < KK; ++kk)
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {   // nb innermost: independent accumulators alternate
-                u32x4 raw = lds_read128(lds + kslot + nb * 32 * G::ROW + k_roff[kk]);
+                u32x4 raw = lds_read128(k_rptr[kk] + kslot + nb * 32 * G::ROW);
                 sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
             }
     };
@@ -324,7 +334,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
                 for (int db = 0; db < DB; ++db) {
                     // k-slots 0..3 / 4..7 of this lane <-> key rows base+g*4+0..3 / base+8+g*4+0..3
-                    const lds_ptr p0 = lds + vslot + (nb * 32 + ks * 16) * G::ROW + v_roff[db];
+                    const lds_ptr p0 = v_rptr[db] + vslot + (nb * 32 + ks * 16) * G::ROW;
                     i16x4 lo = lds_read_tr16(p0);
                     i16x4 hi = lds_read_tr16(p0 + 8 * G::ROW);
                     i16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
