@@ -108,6 +108,33 @@ def test_rising_maxima_exercise_the_rescale():
     check(q, k.flip(2).contiguous(), v, "f16", tile=(64, 64), tag="falling maxima")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("causal", [False, True])
+def test_wide_logit_ranges_exercise_the_lazy_reference(dtype, causal):
+    """The reference of the exponentials is raised only when a tile's weights sum past 2^8: drive it
+    with logits whose spread is far beyond that (near one-hot softmax rows, weights that overflow FP32
+    against a stale reference) and with logits that creep up by less than the threshold per tile."""
+    D, S = 128, 700
+    for std in (3.0, 6.0):                         # logits of standard deviation 9 and 36
+        # (value rows of standard deviation 1/2: a near one-hot row returns a value row, and one rounding
+        # of an FP16 output of magnitude >= 4 would by itself use up the tolerance of 2e-3)
+        q, k, v = make_qkv(1, 3, S, D, dtype, seed=41, qk_std=std, v_std=0.5)
+        for tile in ((128, 32), (128, 64), (64, 32)):
+            check(q, k, v, dtype, tile=tile, causal=causal, tag=f"wide logits std={std}")
+    # one query direction, keys along it with a slope of ~5 log2 units per 32-key tile (below the
+    # threshold of 8) and then a jump of 400 units: weights against the stale reference overflow
+    q = torch.zeros(1, 1, S, D)
+    q[..., 0] = 1.0
+    ramp = torch.arange(S, dtype=torch.float32) * (5.0 / 32.0) * math.log(2.0) * math.sqrt(D)
+    ramp[500:] += 400.0 * math.log(2.0) * math.sqrt(D)
+    k = torch.zeros(1, 1, S, D)
+    k[..., 0] = ramp.view(1, 1, S)
+    tdt = torch.float16 if dtype == "f16" else torch.bfloat16
+    _, _, v = make_qkv(1, 1, S, D, dtype, seed=42, v_std=0.5)
+    check(q.to(tdt), k.to(tdt), v, dtype, tile=(128, 32), causal=causal, tag="creeping then jumping logits")
+    check(q.to(tdt), k.to(tdt).flip(2).contiguous(), v, dtype, tile=(128, 64), causal=causal, tag="falling logits")
+
+
 def test_closed_forms_on_device():
     S, D = 197, 64
     _, k, v = make_qkv(1, 2, S, D, "bf16", seed=41)
