@@ -146,7 +146,6 @@ unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, in
  *   q, k, v, o, dout : [B, H, S, D] as for tiled_sdpa_fwd; o and lse are that call's outputs for the
  *                      same q, k, v, scale and flags (lse is required here).
  *   dq, dk, dv       : [B, H, S, D], same type; every element is overwritten.  Must not alias inputs.
- *   D                : 64 or 128 (other head dims: TSDPA_ERR_UNSUPPORTED_D).
  *   flags            : TSDPA_FLAG_CAUSAL or 0.
  *   workspace        : device memory, 16-byte aligned, at least tiled_sdpa_bwd_workspace_bytes(B, H, S)
  *                      bytes (two FP32 values per query row); caller-owned, used only during this call's

@@ -13,7 +13,9 @@ namespace tsdpa {
 // and runs best on 32-row tiles.
 template <int D> struct BwdShape;
 template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 64, 64}; };
+template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 32, 64}; };
 template <> struct BwdShape<128> { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 32, 64}; };
+template <> struct BwdShape<160> { static constexpr int NW = 4, WPS = 2, TS[3] = {32, 32, 32}; };   // 512-byte LDS rows
 
 template <typename T, int D, int MODE>
 int launch_bwd_pass(const BwdLaunchArgs &a)
@@ -41,7 +43,7 @@ template <typename T, int D>
 int launch_bwd(const BwdLaunchArgs &a)
 {
     const long long rows = (long long)a.BH * a.S;
-    const long long threads = (rows + kBwdStatPad) * 16;
+    const long long threads = (rows + kBwdStatPad) * (D <= 128 ? 16 : 32);
     hipLaunchKernelGGL((sdpa_bwd_prepare_kernel<T, D>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, a.stream,
                        (const T *)a.o, (const T *)a.dout, a.lse, a.delta, a.lse2, rows);
     int err = (int)hipGetLastError();

@@ -32,17 +32,20 @@
 
 namespace tsdpa {
 
-// LDS geometry of a streamed tile: TS rows of D 16-bit values, rows DG*2 bytes apart.  Chunk c of row
+// LDS geometry of a streamed tile: TS rows of D 16-bit values, rows DG*2 bytes apart (DG = D rounded up
+// to a power of two; the chunks past D are never fetched, as in the forward kernel).  Chunk c of row
 // r sits at c ^ swz(r).  Row-wise reads have 16 lanes fetch one chunk index of 16 consecutive rows:
 // swz is a bijection of the row bits that select the bank group, so they spread over all banks.
 // Transposing reads have 32 lanes fetch one 64-byte block (4 chunks) of 4 consecutive rows: bits
 // 3:2 of swz (bit 2 when a row has only two blocks) come from the low row bits, so the four rows
 // land in different blocks.
 template <int D, int TS> struct BwdGeom {
-    static_assert(D == 64 || D == 128, "backward pass: head dims 64 and 128");
-    static constexpr int DG = D;
-    static constexpr int ROW = DG * 2;
+    static_assert(D == 64 || D == 96 || D == 128 || D == 160, "head dims of the paper's grid");
+    static constexpr int DG = D <= 64 ? 64 : (D <= 128 ? 128 : 256);   // LDS row geometry: next power of two
+    static constexpr int ROW = DG * 2;              // bytes per LDS row
+    static constexpr int GROW = D * 2;              // bytes per row in global memory
     static constexpr int TILE = TS * ROW;
+    static constexpr int GTILE = TS * GROW;
     static constexpr int STATS = 2 * TS * 4;        // LSE then Delta of a tile's rows (keys-resident passes)
     static constexpr int LDS_BYTES = 4 * TILE + 2 * STATS;   // T1 slots 0,1, T2 slots 0,1, statistics slots 0,1
     static __host__ __device__ constexpr int swz(int r) {
@@ -50,7 +53,7 @@ template <int D, int TS> struct BwdGeom {
     }
 };
 
-// Delta_i = <dO_i, O_i> and LSE_i in log2 units, one row per group of 16 (D <= 128) lanes; the
+// Delta_i = <dO_i, O_i> and LSE_i in log2 units, one row per group of 16 (D <= 128) or 32 lanes; the
 // kBwdStatPad entries after the last row are set to zero.
 template <typename T, int D>
 __global__ void __launch_bounds__(256)
@@ -59,7 +62,7 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     using vec8 = typename Elem<T>::vec8;
-    constexpr int LPR = 16;                        // lanes per row; lanes >= D/8 idle
+    constexpr int LPR = D <= 128 ? 16 : 32;        // lanes per row; lanes >= D/8 idle
     const long long row = ((long long)blockIdx.x * 256 + threadIdx.x) / LPR;
     const int part = threadIdx.x % LPR;
     float sum = 0.f;
@@ -100,7 +103,8 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     constexpr bool KEYS_RES = MODE != BWD_DQ;
     constexpr bool NEED_DP = MODE != BWD_DV;      // dP product and Delta
     constexpr int RM = NW * 32;                   // resident rows per workgroup
-    constexpr int CPR = G::DG / 8;                // 16-byte chunks per row
+    constexpr int CPR = G::DG / 8;                // 16-byte chunks per LDS row
+    constexpr int GCPR = D / 8;                   // ... of which this many hold data
     constexpr int NLD = TS * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
     static_assert(NLD >= 1 && (TS * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
     constexpr int NB = TS / 32, KK = D / 16, DB = D / 32;
@@ -164,17 +168,19 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // ---- streamed tiles HBM -> LDS, as in the forward kernel: a descriptor per tensor covers this
     // head's S rows (rows >= S read as zeros), lane `lane` of load `it` fills LDS chunk
     // (it*NW + wave)*64 + lane with the global chunk the swizzle maps there
-    const auto t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::ROW, 0x00020000);
-    const auto t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::ROW, 0x00020000);
+    const auto t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::GROW, 0x00020000);
+    const auto t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::GROW, 0x00020000);
+    constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
     int goff[NLD];
 #pragma unroll
     for (int it = 0; it < NLD; ++it) {
         const int p = (it * NW + wave) * 64 + lane;
         const int r = p / CPR, cp = p % CPR;
-        goff[it] = r * G::ROW + ((cp ^ G::swz(r)) << 4);
+        const int gc = cp ^ G::swz(r);            // global chunk that belongs at LDS chunk cp
+        goff[it] = gc < GCPR ? r * G::GROW + (gc << 4) : kNoFetch;
     }
     auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) __attribute__((always_inline)) {
-        const int soff = (j < j1 ? j : nT) * G::TILE;     // a tile past the range: outside the descriptor, zeros
+        const int soff = (j < j1 ? j : nT) * G::GTILE;    // a tile past the range: outside the descriptor, zeros
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
@@ -352,7 +358,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         for (int i = 0; i < 32 / RPI; ++i) {
             const int r = i * RPI + lane / CPR, cc = lane % CPR;
             const u32x4 val = lds_read128(ow + r * G::ROW + ((cc ^ (r & CMASK)) << 4));
-            if (row0 + r < S) *(u32x4 *)(dst + head_off + (size_t)(row0 + r) * D + cc * 8) = val;
+            if (row0 + r < S && cc < GCPR) *(u32x4 *)(dst + head_off + (size_t)(row0 + r) * D + cc * 8) = val;
         }
     };
     static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");

@@ -54,8 +54,12 @@ int launch_bf16_d160(int tile_m, int tile_n, const LaunchArgs &a);
 
 // Backward pass: statistics kernel, then the dV, dK (keys resident) and dQ (queries resident) passes.
 int launch_bwd_f16_d64(const BwdLaunchArgs &a);
+int launch_bwd_f16_d96(const BwdLaunchArgs &a);
 int launch_bwd_f16_d128(const BwdLaunchArgs &a);
+int launch_bwd_f16_d160(const BwdLaunchArgs &a);
 int launch_bwd_bf16_d64(const BwdLaunchArgs &a);
+int launch_bwd_bf16_d96(const BwdLaunchArgs &a);
 int launch_bwd_bf16_d128(const BwdLaunchArgs &a);
+int launch_bwd_bf16_d160(const BwdLaunchArgs &a);
 
 }  // namespace tsdpa

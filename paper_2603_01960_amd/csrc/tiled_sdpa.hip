@@ -282,7 +282,6 @@ int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, c
                    void *workspace, unsigned long long workspace_bytes, void *stream)
 {
     if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
-    if (D != 64 && D != 128) return TSDPA_ERR_UNSUPPORTED_D;
     int st = validate_shape(B, H, S, D, dtype);
     if (st != TSDPA_OK) return st;
     // the statistics arrays are addressed through a 32-bit byte range
@@ -313,8 +312,21 @@ int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, c
     a.causal = (flags & TSDPA_FLAG_CAUSAL) ? 1 : 0;
     a.stream = (hipStream_t)stream;
     int err;
-    if (dtype == TSDPA_F16) err = D == 64 ? tsdpa::launch_bwd_f16_d64(a) : tsdpa::launch_bwd_f16_d128(a);
-    else err = D == 64 ? tsdpa::launch_bwd_bf16_d64(a) : tsdpa::launch_bwd_bf16_d128(a);
+    if (dtype == TSDPA_F16) {
+        switch (D) {
+            case 64: err = tsdpa::launch_bwd_f16_d64(a); break;
+            case 96: err = tsdpa::launch_bwd_f16_d96(a); break;
+            case 128: err = tsdpa::launch_bwd_f16_d128(a); break;
+            default: err = tsdpa::launch_bwd_f16_d160(a); break;
+        }
+    } else {
+        switch (D) {
+            case 64: err = tsdpa::launch_bwd_bf16_d64(a); break;
+            case 96: err = tsdpa::launch_bwd_bf16_d96(a); break;
+            case 128: err = tsdpa::launch_bwd_bf16_d128(a); break;
+            default: err = tsdpa::launch_bwd_bf16_d160(a); break;
+        }
+    }
     return err == 0 ? TSDPA_OK : TSDPA_ERR_LAUNCH;
 }
 

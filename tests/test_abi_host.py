@@ -149,8 +149,10 @@ def test_kv_workspace_size_and_default_splits(lib):
 
 @pytest.mark.parametrize("kwargs,expect", [
     (dict(dtype=3), DTYPE),
-    (dict(D=96), BAD_D),                           # the backward pass covers D = 64 and 128
-    (dict(D=160), BAD_D),
+    (dict(D=80), BAD_D),
+    (dict(D=192), BAD_D),
+    (dict(D=96, q=None), NULL),                    # 96 and 160 pass the head-dim check
+    (dict(D=160, ws=None), WORKSPACE),
     (dict(S=-1), SHAPE),
     (dict(B=1 << 10, H=1 << 10, S=1 << 10), SHAPE),    # statistics arrays beyond a 32-bit byte range
     (dict(S=0, q=None, dq=None, ws=None), OK),

@@ -171,8 +171,18 @@ def test_nothing_is_read_past_the_end_of_the_inputs():
         compare([g.cpu() for g in got], ref, "f16", "guarded")
 
 
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("D", [96, 160])
+def test_head_dims_96_and_160(D, dtype, causal):
+    for S in (1, 33, 64, 130, 197, 300, 517, 1024):
+        q, k, v = make_qkv(1, 3, S, D, dtype, seed=12600 + S + D)
+        do = make_dout(q.shape, dtype, 12700 + S)
+        check_bwd(q, k, v, do, dtype, causal=causal, tag=f"D={D} S={S}")
+
+
 def test_unsupported_head_dims_are_refused():
-    x = torch.zeros(1, 1, 16, 96, dtype=torch.float16, device="cuda")
+    x = torch.zeros(1, 1, 16, 80, dtype=torch.float16, device="cuda")
     lse = torch.zeros(1, 1, 16, dtype=torch.float32, device="cuda")
     with pytest.raises(binding.TiledSdpaError) as e:
         binding.sdpa_backward(x, x, x, x, x, lse)
