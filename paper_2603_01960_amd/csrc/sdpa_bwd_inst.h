@@ -8,20 +8,20 @@
 namespace tsdpa {
 
 // Tile shapes, from timings on MI355X: 32*NW resident rows per workgroup, TS streamed rows per tile for
-// the dQ / dK / dV pass, and the wavefronts per SIMD the register budget is sized for.  At D = 128 the
+// the dQ / dK / dV pass, and the wavefronts per SIMD the register budget of each is sized for.  At D = 128 the
 // dK pass (two resident operand sets, one output, per-row statistics) is the tightest on registers
 // and runs best on 32-row tiles.
 template <int D> struct BwdShape;
-template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 64, 64}; };
-template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 32, 64}; };
-template <> struct BwdShape<128> { static constexpr int NW = 4, WPS = 2, TS[3] = {64, 32, 64}; };
-template <> struct BwdShape<160> { static constexpr int NW = 4, WPS = 2, TS[3] = {32, 32, 32}; };   // 512-byte LDS rows
+template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 64, 64}; };
+template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 32, 64}; };
+template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 32, 64}; };
+template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {32, 32, 32}; };   // 512-byte LDS rows
 
 template <typename T, int D, int MODE>
 int launch_bwd_pass(const BwdLaunchArgs &a)
 {
     using Sh = BwdShape<D>;
-    constexpr int NW = Sh::NW, TS = Sh::TS[MODE], WPS = Sh::WPS;
+    constexpr int NW = Sh::NW, TS = Sh::TS[MODE], WPS = Sh::WPS[MODE];
     auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, MODE>;
     constexpr int lds_bytes = BwdGeom<D, TS>::LDS_BYTES;
     static std::once_flag once;

@@ -273,8 +273,8 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             products(cur, nb, rf1, sacc);
             if constexpr (NEED_DP) products(T2BASE + cur, nb, rf2, dpacc);
             // the 16 streamed rows this lane meets in the block come in 4 runs of 4 consecutive rows; in the
-            // keys-resident passes their statistics are read from the LDS run by run (the scheduling
-            // barriers keep the compiler from fetching all of them ahead, which costs 32 registers)
+            // keys-resident passes their statistics are read from the LDS run by run (in the dK pass
+            // scheduling barriers keep the compiler from fetching all of them ahead, which costs 32 registers)
             const lds_ptr sp = lds + stat_slot(cur) + (nb * 32 + g * 4) * 4;
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
@@ -298,7 +298,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                     }
                     xb[nb][i >> 3][i & 7] = (T)x;
                 }
-                if constexpr (KEYS_RES) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (MODE == BWD_DK) __builtin_amdgcn_sched_barrier(0);
             }
         }
         accumulate(MODE == BWD_DV ? T2BASE + cur : cur, xb, oacc);
