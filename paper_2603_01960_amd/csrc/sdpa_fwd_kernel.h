@@ -310,7 +310,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
         const int key0 = j * TN + g * 4;
-        float psum[4] = {0.f, 0.f, 0.f, 0.f};
+        float psum[4];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -319,7 +319,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 if constexpr (MASK) {
                     if (key0 + nb * 32 + (i >> 2) * 8 + (i & 3) > klim) p = 0.f;
                 }
-                psum[i & 3] += p;
+                if (nb == 0 && i < 4) psum[i] = p;        // four partial sums: short dependency chains
+                else psum[i & 3] += p;
                 pb[nb][i >> 3][i & 7] = (T)p;
             }
         return (psum[0] + psum[1]) + (psum[2] + psum[3]);
