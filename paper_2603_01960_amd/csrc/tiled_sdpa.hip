@@ -24,16 +24,13 @@ void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
 {
     (void)BH;
     // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts) win at every
-    // configuration measured.  K/V tiles: 32 rows when there are only a few tiles per head (the loop
-    // fills sooner, the ragged tail wastes less), 64 rows from S = 512 at D = 64.  At D = 96 and 128 the
-    // 32-row tile is the one that fits three wavefronts per SIMD and is 1-4 % ahead on long sequences,
-    // except under the causal mask, where its finer diagonal does not pay for the extra barriers.
-    // At D = 160 only the 32-row tile leaves room for two workgroups per CU (512-byte LDS rows).
-    *tm = 128;
-    *tn = S >= 512 ? 64 : 32;
-    if (D == 160 || D == 96) *tn = 32;
-    if (D == 128 && !causal && S >= 1024) *tn = 32;
-    if (S <= 64) *tm = 64;
+    // configuration measured.  K/V tiles of 32 rows are the ones whose loop fits three (D = 96, 128)
+    // or four (D = 64) wavefronts per SIMD; they are level with or ahead of 64-row tiles everywhere
+    // (1-6 %) except under the causal mask at D = 64 and 128, where the finer diagonal does not pay for
+    // the extra barriers.  At D = 160 only the 32-row tile leaves room for two workgroups per CU.
+    *tm = S <= 64 ? 64 : 128;
+    *tn = 32;
+    if (causal && S >= 512 && (D == 64 || D == 128)) *tn = 64;
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
@@ -91,7 +88,7 @@ int validate_shape_kv(int B, int H, int Sq, int Skv, int D, int dtype, unsigned 
 void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 {
     *tm = Sq <= 64 ? 64 : 128;
-    *tn = (Skv >= 512 && D != 160 && D != 96) ? 64 : 32;
+    *tn = (Skv >= 512 && D != 160 && D != 96) ? 64 : 32;   // decoding shapes are bound by the cache read, not by the loop
 }
 
 }  // namespace
