@@ -37,7 +37,7 @@ enum {
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64, 96, 128 or 160                             */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
     TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}, or
-                                    tile_n = 128 at D = 160 (does not fit the LDS)          */
+                                    tile_n = 128 at D > 64 (register and LDS budget)        */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
     TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split, tiled_sdpa_bwd: workspace NULL,
@@ -85,7 +85,7 @@ int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *
 /*
  * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
  * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
- * {32,64,128}; tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
+ * {32,64} and, at D = 64, 128; tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
  * tiled_sdpa_fwd uses.  The result does not depend on the tile choice beyond rounding order.
  */
 int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,

@@ -25,7 +25,9 @@ int launch_one(const LaunchArgs &a)
 {
     constexpr int WPS = waves_per_simd<D, NW, TN>();
     auto kern = sdpa_fwd_kernel<T, D, NW, TN, WPS, KV>;
-    constexpr int lds_bytes = TileGeom<D, TN>::LDS_BYTES;
+    // K/V tile slots during the loop, one 32 x D block per wavefront for the output transpose after it
+    constexpr int stage_bytes = NW * 32 * TileGeom<D, TN>::ROW;
+    constexpr int lds_bytes = TileGeom<D, TN>::LDS_BYTES > stage_bytes ? TileGeom<D, TN>::LDS_BYTES : stage_bytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -59,12 +61,12 @@ int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a)
         case 64032: return launch_one<T, D, 2, 32>(a);
         case 64064: return launch_one<T, D, 2, 64>(a);
         case 64128:
-            if constexpr (TileGeom<D, 128>::LDS_BYTES <= kLdsPerCU) return launch_one<T, D, 2, 128>(a);
-            else return (int)hipErrorInvalidValue;   // D = 160: four 128-row tiles exceed the LDS
+            if constexpr (D == 64) return launch_one<T, D, 2, 128>(a);
+            else return (int)hipErrorInvalidValue;   // 128-row K/V tiles only at D = 64 (register budget)
         case 128032: return launch_one<T, D, 4, 32>(a);
         case 128064: return launch_one<T, D, 4, 64>(a);
         case 128128:
-            if constexpr (TileGeom<D, 128>::LDS_BYTES <= kLdsPerCU) return launch_one<T, D, 4, 128>(a);
+            if constexpr (D == 64) return launch_one<T, D, 4, 128>(a);
             else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }

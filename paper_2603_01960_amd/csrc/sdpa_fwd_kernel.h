@@ -265,13 +265,25 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) sacc[nb][i] = 0.f;
+        if constexpr (NB == 1 && KK <= 8) {
+            // 32-row tiles (the register-lean instantiations): all operand reads first, then the MFMA
+            // chain.  The scheduling barrier keeps the compiler from sinking each read next to its MFMA,
+            // where the LDS latency would be paid once per MFMA instead of once per tile (+2-4 %).
+            u32x4 kb[KK];
 #pragma unroll
-        for (int kk = 0; kk < KK; ++kk)
+            for (int kk = 0; kk < KK; ++kk) kb[kk] = lds_read128(k_rptr[kk] + kslot);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {   // nb innermost: independent accumulators alternate
-                u32x4 raw = lds_read128(k_rptr[kk] + kslot + nb * 32 * G::ROW);
-                sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
-            }
+            for (int kk = 0; kk < KK; ++kk) sacc[0] = E::mfma(__builtin_bit_cast(vec8, kb[kk]), qf[kk], sacc[0]);
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < KK; ++kk)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {   // nb innermost: independent accumulators alternate
+                    u32x4 raw = lds_read128(k_rptr[kk] + kslot + nb * 32 * G::ROW);
+                    sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
+                }
+        }
     };
 
     // Eq. 2 on one tile of scores, for the rows whose weights overflowed the limit (`over`; the two lanes
@@ -343,13 +355,25 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 }
     };
 
-    // ---- main loop, unrolled by two so that the LDS slots alternate by name.  In step j the LDS holds
-    // K(j) and V(j); K(j+1) and V(j+1) are in flight into the other slots, whose last readers finished
-    // before the barrier that ended step j-1.  Overlap of matrix and vector work comes from the two
-    // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
-    // ahead cost 32 registers and measured 4 % slower).
     f32x16 sacc[NB];
     vec8 pb[NB][2];
+    // weights of tile j (with the lazy reference), this lane's share of their sum added to l_run
+    auto softmax_tile = [&](int j, auto mask_tag) __attribute__((always_inline)) {
+        float ps = exponentials(sacc, j, pb, mask_tag);
+        const bool over = !(ps <= lazy_limit);               // also catches inf (first tile) and NaN
+        if (__builtin_amdgcn_ballot_w64(over) != 0) {        // wavefront-uniform and rare
+            raise_reference(sacc, j, mask_tag, over);
+            ps = exponentials(sacc, j, pb, mask_tag);
+        }
+        l_run += ps;
+    };
+    using P0 = std::integral_constant<int, 0>;
+    using P1 = std::integral_constant<int, 1>;
+    // ---- main loop, unrolled by two so that the LDS slots alternate by name.  In step j the LDS holds
+    // K(j) and V(j); K(j+1) and V(j+1) are in flight into the other slots, whose last readers finished
+    // before the barrier that ended step j-1.  Overlap of matrix and vector work comes from the
+    // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
+    // ahead cost 32 registers and measured 4 % slower).
     if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
     load_tile(k_rsrc, k_goff, t0, lds + KSLOT0);
     load_tile(v_rsrc, v_goff, t0, lds + VSLOT0);
@@ -368,19 +392,11 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         __builtin_amdgcn_s_setprio(1);
         scores(PAR ? KSLOT1 : KSLOT0, sacc);
         __builtin_amdgcn_s_setprio(0);
-        float ps = exponentials(sacc, j, pb, mask_tag);
-        const bool over = !(ps <= lazy_limit);               // also catches inf (first tile) and NaN
-        if (__builtin_amdgcn_ballot_w64(over) != 0) {        // wavefront-uniform and rare
-            raise_reference(sacc, j, mask_tag, over);
-            ps = exponentials(sacc, j, pb, mask_tag);
-        }
-        l_run += ps;
+        softmax_tile(j, mask_tag);
         accumulate(PAR ? VSLOT1 : VSLOT0, pb);
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
-    using P0 = std::integral_constant<int, 0>;
-    using P1 = std::integral_constant<int, 1>;
     // tiles below nfull need no mask: they run in pairs through the unmasked step; the few tiles
     // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
     // masked path, which is also correct for a tile that turns out to need no mask
@@ -429,7 +445,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const float inv = 1.0f / l_tot;
     if (lse != nullptr && g == 0 && qrow < S)
         lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
-    static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");
+    // (the launcher sizes the dynamic LDS for the larger of the tile slots and this staging area)
     {
         constexpr int CMASK = CPR - 1;                // chunks per row is 8 or 16
         const lds_ptr ow = lds + wave * (32 * G::ROW);

@@ -16,7 +16,10 @@ constexpr int kVersion = 200;  // 0.2.0
 bool valid_tile(int tm, int tn, int D)
 {
     if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64 || tn == 128)) return false;
-    return !(D == 160 && tn == 128);   // four 128 x 512-byte tiles do not fit the 160 KB LDS
+    // 128-row K/V tiles only at D = 64: their score accumulators alone take 64 registers, which beside the
+    // output accumulator of a larger head dim no longer leaves a loop without spills (and at D = 160 four
+    // such tiles do not fit the LDS)
+    return tn != 128 || D == 64;
 }
 
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
@@ -106,7 +109,7 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_BAD_DTYPE: return "bad dtype: expected TSDPA_F16 or TSDPA_BF16";
         case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64, 96, 128 or 160";
         case TSDPA_ERR_MISALIGNED: return "misaligned pointer: q, k, v, o need 16-byte, lse 4-byte alignment";
-        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128}, or both 0";
+        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64} (128 at D = 64), or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
         case TSDPA_ERR_WORKSPACE: return "split workspace is null, misaligned or too small";

@@ -73,6 +73,8 @@ P = 0x1000  # fake, aligned, never dereferenced: every case below fails validati
     (dict(tile_m=128, tile_n=0), TILE),
     (dict(tile_m=128, tile_n=256), TILE),
     (dict(D=160, tile_m=128, tile_n=128), TILE),
+    (dict(D=128, tile_m=64, tile_n=128), TILE),     # 128-row K/V tiles exist at D = 64 only
+    (dict(D=64, tile_m=64, tile_n=128, S=0), OK),
     (dict(D=160, tile_m=64, tile_n=64, S=0), OK),
     (dict(S=1 << 23, D=128), SHAPE),
     (dict(scale=math.inf), SCALE),
@@ -193,7 +195,7 @@ def test_default_tile_is_a_legal_tile(lib):
     for S in (1, 32, 64, 197, 1024, 16384):
         for D in (64, 96, 128, 160):
             tm, tn = binding.default_tile(2, 4, S, D, binding.BF16)
-            assert tm in (64, 128) and tn in (32, 64, 128) and not (D == 160 and tn == 128)
+            assert tm in (64, 128) and tn in (32, 64, 128) and not (D != 64 and tn == 128)
     with pytest.raises(binding.TiledSdpaError):
         binding.default_tile(1, 1, 16, 72, 0)
 
