@@ -121,23 +121,47 @@ def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fi
     }
 
 
-def time_batched(pkg, torch, name, dtype, n, warmup):
+def time_batched(pkg, torch, name, dtype, n, warmup, rotate=1):
     """Per-launch time with the launches issued back to back between ONE pair of events: for kernels
-    of a few tens of microseconds the event pair of time_workload() mostly measures launch latency."""
+    of a few tens of microseconds the event pair of time_workload() mostly measures launch latency.
+    rotate > 1 cycles the launches over that many copies of (Q, K, V, O) in distinct memory, so that a
+    launch finds none of its tensors in the L2 or in the 256 MB memory-side cache (a cache-cold figure
+    for the workloads whose tensors would otherwise stay resident between launches)."""
     from paper_2603_01960_amd.workloads import make_workload
     w, q, k, v = make_workload(name, dtype)
-    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
-    o = torch.empty_like(qd)
-    for _ in range(warmup):
+    sets = []
+    for _ in range(rotate):
+        qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+        sets.append((qd, kd, vd, torch.empty_like(qd)))
+    for i in range(max(warmup, rotate)):
+        qd, kd, vd, o = sets[i % rotate]
         pkg.sdpa(qd, kd, vd, out=o)
     torch.cuda.synchronize()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     a.record()
-    for _ in range(n):
+    for i in range(n):
+        qd, kd, vd, o = sets[i % rotate]
         pkg.sdpa(qd, kd, vd, out=o)
     b.record()
     torch.cuda.synchronize()
     return w, a.elapsed_time(b) / n
+
+
+def hbm_copy_ceiling(torch, mib=1024, steps=10):
+    """GB/s (read + write) of a plain device-to-device copy too large for any cache: what a pure
+    stream sustains on this GPU right now, next to the published 8 TB/s."""
+    n = mib * (1 << 20)
+    src = torch.empty(n, dtype=torch.uint8, device="cuda").fill_(3)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return round(2 * n / (a.elapsed_time(b) / steps) / 1e6, 1)
 
 
 def mfma_ceilings(pkg, torch, dtype, iters=4000):
@@ -147,7 +171,7 @@ def mfma_ceilings(pkg, torch, dtype, iters=4000):
     stream = torch.cuda.current_stream().cuda_stream
     code = pkg.F16 if dtype == "f16" else pkg.BF16
     out = {}
-    for label, rnd in (("random_operands", True), ("constant_operands", False)):
+    for label, rnd in (("random_operands", 1), ("constant_operands", 0), ("random_operands_plus_loop_mix", 2)):
         for _ in range(2):
             pkg.probe_mfma(code, rnd, iters, sink.data_ptr(), stream)
         torch.cuda.synchronize()
@@ -376,6 +400,8 @@ def main():
         ceil = mfma_ceilings(pkg, torch, dtype)
         out["mfma_only_ceiling_tflops"] = ceil
         out["frac_of_mfma_only_ceiling_random_operands"] = round(kern_tflops / ceil["random_operands"], 4)
+        out["frac_of_loop_mix_ceiling"] = round(kern_tflops / ceil["random_operands_plus_loop_mix"], 4)
+        out["hbm_copy_ceiling_GBs"] = hbm_copy_ceiling(torch)
 
     if args.all_workloads:
         others = {}
@@ -386,6 +412,13 @@ def main():
                     "ms_per_launch_back_to_back": round(ms, 5),
                     "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
                     "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
+                sets = -(-(1 << 30) // int(ww.compulsory_bytes(2)))      # >= 1 GiB of distinct tensors in rotation
+                if 1 < sets <= 64:
+                    _, ms = time_batched(pkg, torch, name, dt, max(4 * sets, args.steps), args.warmup, rotate=sets)
+                    others[f"{name}_{dt}"]["cache_cold"] = {
+                        "buffer_sets_in_rotation": sets, "ms_per_launch": round(ms, 5),
+                        "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
+                        "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
         out["all_workloads"] = others
 
     if not args.no_cpu_baseline:

@@ -168,7 +168,10 @@ unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S);
  * wavefronts, `iters` x 64 MFMAs per wavefront -- so the caller can time what the matrix pipe
  * sustains with no memory traffic.  random_operands != 0 fills the operand registers with random
  * signs and mantissas (the switching activity of real data, under which the chip lowers its
- * clock); 0 uses constant ones.  sink: device buffer of at least 512*256 floats, overwritten.
+ * clock); 0 uses constant ones; 2 is the random-operand stream with the rest of the attention
+ * loop's instruction mix added at the loop's own ratios and independent of the MFMAs (per MFMA one
+ * 16-byte-per-lane LDS read and 3.7 vector instructions, a quarter of them exponentials): the rate
+ * that mix sustains when nothing ever waits for anything.  sink: device buffer of at least 512*256 floats, overwritten.
  * flops (host pointer, may be NULL) receives the flop count of the launch.  The Section 4.2.3
  * policy of measuring on an otherwise idle GPU applies.  Returns a status code; iters = 0 only
  * reports flops.

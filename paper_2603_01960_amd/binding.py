@@ -110,12 +110,15 @@ def kv_workspace_bytes(B: int, H: int, Sq: int, D: int, splits: int) -> int:
     return int(load_library().tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits))
 
 
-def probe_mfma(dtype: int, random_operands: bool, iters: int, sink=None, stream=None) -> float:
-    """Enqueue the MFMA-only stream (see tiled_sdpa_probe_mfma); returns its flop count.
+def probe_mfma(dtype: int, random_operands, iters: int, sink=None, stream=None) -> float:
+    """Enqueue the MFMA stream (see tiled_sdpa_probe_mfma); returns its flop count.
+
+    ``random_operands``: False/0 constant operands, True/1 random ones, 2 random ones plus the
+    attention loop's LDS-read and vector-ALU mix.
 
     With ``sink=None`` and ``iters=0`` nothing is launched (flop count only)."""
     flops = ctypes.c_double(0.0)
-    st = load_library().tiled_sdpa_probe_mfma(dtype, 1 if random_operands else 0, iters,
+    st = load_library().tiled_sdpa_probe_mfma(dtype, int(random_operands), iters,
                                               sink if sink is not None else 0x1000, ctypes.byref(flops), stream)
     if st != 0:
         raise TiledSdpaError(st, status_string(st))

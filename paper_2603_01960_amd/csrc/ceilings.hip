@@ -69,6 +69,74 @@ __global__ void __launch_bounds__(256) mfma_stream(float *sink, int iters, int r
 #endif
 }
 
+// The same MFMA stream with the other work of the attention kernel's loop mixed in at the kernel's own
+// ratios (C4 profile: per MFMA one 16-byte-per-lane LDS operand read and 3.7 vector instructions, a
+// quarter of them exponentials), all of it independent of the MFMAs: what the chip sustains for that
+// instruction mix when nothing ever waits.  Operands are random as above; the LDS holds random data.
+template <bool BF16>
+__global__ void __launch_bounds__(256) mfma_mix_stream(float *sink, int iters)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    __shared__ __attribute__((aligned(16))) uint32_t tile[4096];      // 16 KiB, one K tile's worth
+    for (int i = threadIdx.x; i < 4096; i += 256) tile[i] = mix(i * 977u + blockIdx.x);
+    __syncthreads();
+    const uint32_t lds_addr = (uint32_t)(size_t)(__attribute__((address_space(3))) uint32_t *)tile + (threadIdx.x & 63) * 16;
+    u32x4 ra[8], rb[8];
+    const uint32_t expo = BF16 ? 0x3f003f00u : 0x38003800u;
+    const uint32_t keep = BF16 ? 0x807f807fu : 0x83ff83ffu;
+#pragma unroll
+    for (int f = 0; f < 8; ++f)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const uint32_t h = mix((blockIdx.x * 256u + threadIdx.x) * 64u + f * 8u + e);
+            ra[f][e] = (h & keep) | expo;
+            rb[f][e] = (mix(h) & keep) | expo;
+        }
+    f32x16 acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
+    u32x4 d0 = {0u, 0u, 0u, 0u}, d1 = d0, d2 = d0, d3 = d0;   // landing registers of the LDS reads
+    float x0 = 0.3f + (threadIdx.x & 63), x1 = 0.7f, x2 = 1.1f, x3 = 0.1f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+#pragma unroll
+            for (int r = 0; r < 8; r += 4)            // 8 reads of 1 KiB per 8 MFMAs, walking the tile
+                asm volatile("ds_read_b128 %0, %4 offset:%5\n ds_read_b128 %1, %4 offset:%6\n"
+                             "ds_read_b128 %2, %4 offset:%7\n ds_read_b128 %3, %4 offset:%8"
+                             : "+v"(d0), "+v"(d1), "+v"(d2), "+v"(d3)
+                             : "v"(lds_addr), "n"(((u * 8 + r) % 16) * 1024), "n"(((u * 8 + r + 1) % 16) * 1024),
+                               "n"(((u * 8 + r + 2) % 16) * 1024), "n"(((u * 8 + r + 3) % 16) * 1024));
+#pragma unroll
+            for (int f = 0; f < 8; ++f) {
+                if constexpr (BF16)
+                    acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ra[f]),
+                                                                        __builtin_bit_cast(bf16x8, rb[(f + u) & 7]),
+                                                                        acc[f & 3], 0, 0, 0);
+                else
+                    acc[f & 3] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, ra[f]),
+                                                                       __builtin_bit_cast(f16x8, rb[(f + u) & 7]),
+                                                                       acc[f & 3], 0, 0, 0);
+#pragma unroll
+                for (int v = f * 30 / 8; v < (f + 1) * 30 / 8; ++v) {      // 30 vector instructions per 8 MFMAs
+                    if ((v & 3) == 0) asm volatile("v_exp_f32 %0, %1" : "+v"(x3) : "v"(x0));
+                    else asm volatile("v_fma_f32 %0, %1, %2, %0" : "+v"(x0) : "v"(x1), "v"(x2));
+                }
+            }
+        }
+    }
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // every read has landed before its register dies
+    float s = x0 + x3 + (float)(d0[0] ^ d1[0] ^ d2[0] ^ d3[0]);
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) s += acc[n][i];
+    sink[blockIdx.x * 256 + threadIdx.x] = s;
+#endif
+}
+
 }  // namespace
 
 extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink,
@@ -79,7 +147,12 @@ extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, 
     if (!sink) return TSDPA_ERR_NULL_PTR;
     if (flops) *flops = (double)kGrid * 4.0 * (double)iters * kMfmaPerIter * 32768.0;
     if (iters == 0) return TSDPA_OK;
-    if (dtype == TSDPA_BF16)
+    if (random_operands == 2) {
+        if (dtype == TSDPA_BF16)
+            hipLaunchKernelGGL(mfma_mix_stream<true>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters);
+        else
+            hipLaunchKernelGGL(mfma_mix_stream<false>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters);
+    } else if (dtype == TSDPA_BF16)
         hipLaunchKernelGGL(mfma_stream<true>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
     else
         hipLaunchKernelGGL(mfma_stream<false>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
