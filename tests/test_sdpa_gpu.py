@@ -246,7 +246,7 @@ def test_mfma_probe_runs_and_reports_its_flops():
     sink = torch.zeros(512 * 256, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     for dt in (binding.F16, binding.BF16):
-        for rnd in (False, True):
+        for rnd in (0, 1, 2):       # constant, random, random + the loop's LDS-read / vector-ALU mix
             flops = binding.probe_mfma(dt, rnd, 10, sink.data_ptr(), stream)
             torch.cuda.synchronize()
             assert flops == 512 * 4 * 10 * 64 * 32768
