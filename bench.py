@@ -27,8 +27,8 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
 # scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", "bf16"): 772.5e6,   # 617.3 MB fetched + 155.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
-    ("C5", "f16"): 594.5e6,    # 516.9 MB + 77.6 MB          (profiles/sdpa_fwd_C5_f16.md)
+    ("C4", "bf16"): 737.7e6,   # 582.5 MB fetched + 155.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
+    ("C5", "f16"): 495.7e6,    # 418.1 MB + 77.6 MB          (profiles/sdpa_fwd_C5_f16.md)
     ("C3", "bf16"): 77.6e6,    # 58.2 MB + 19.4 MB           (profiles/sdpa_fwd_C3_bf16.md)
     ("C2", "f16"): 33.7e6,     # 25.3 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
 }
