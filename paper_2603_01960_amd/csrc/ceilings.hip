@@ -98,7 +98,7 @@ __global__ void __launch_bounds__(256) mfma_mix_stream(float *sink, int iters)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[n][i] = 0.f;
     u32x4 d0 = {0u, 0u, 0u, 0u}, d1 = d0, d2 = d0, d3 = d0;   // landing registers of the LDS reads
-    float x0 = 0.3f + (threadIdx.x & 63), x1 = 0.7f, x2 = 1.1f, x3 = 0.1f;
+    float x0 = 0.3f + (threadIdx.x & 63), x1 = 0.7f, x2 = 1.1f + 0.01f * (threadIdx.x & 63), x3 = 0.1f;   // x0 -> x2 / (1 - x1)
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -122,7 +122,7 @@ __global__ void __launch_bounds__(256) mfma_mix_stream(float *sink, int iters)
 #pragma unroll
                 for (int v = f * 30 / 8; v < (f + 1) * 30 / 8; ++v) {      // 30 vector instructions per 8 MFMAs
                     if ((v & 3) == 0) asm volatile("v_exp_f32 %0, %1" : "+v"(x3) : "v"(x0));
-                    else asm volatile("v_fma_f32 %0, %1, %2, %0" : "+v"(x0) : "v"(x1), "v"(x2));
+                    else asm volatile("v_fma_f32 %0, %0, %1, %2" : "+v"(x0) : "v"(x1), "v"(x2));
                 }
             }
         }
