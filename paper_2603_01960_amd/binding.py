@@ -131,6 +131,30 @@ def tiled_sdpa_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype
                                              float(scale), dtype, stream))
 
 
+
+class _NoGuard:
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        return False
+
+
+_NO_GUARD = _NoGuard()
+
+
+def _guard_and_stream(torch, device):
+    """(context manager that makes ``device`` current for the launch, raw handle of the stream that is
+    current on it).  A short call is dominated by host time, so the usual case -- the tensors live on
+    the current device -- takes no device switch and reads the raw stream handle directly."""
+    current = torch.cuda.current_device()
+    index = current if device.index is None else device.index
+    guard = _NO_GUARD if index == current else torch.cuda.device(index)
+    raw = getattr(torch._C, "_cuda_getCurrentRawStream", None)
+    stream = raw(index) if raw is not None else torch.cuda.current_stream(index).cuda_stream
+    return guard, stream
+
+
 def tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype, stream,
                       tile_m=0, tile_n=0, flags=0) -> int:
     return int(load_library().tiled_sdpa_fwd_ex(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D,
@@ -181,8 +205,8 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    with torch.cuda.device(q.device):
-        stream = torch.cuda.current_stream().cuda_stream
+    guard, stream = _guard_and_stream(torch, q.device)
+    with guard:
         st = tiled_sdpa_fwd_kv(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                lse.data_ptr() if lse is not None else None,
                                B, H, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
@@ -231,8 +255,8 @@ def sdpa_backward(q, k, v, o, dout, lse, causal: bool = False, scale=None, *, wo
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
-    with torch.cuda.device(q.device):
-        stream = torch.cuda.current_stream().cuda_stream
+    guard, stream = _guard_and_stream(torch, q.device)
+    with guard:
         st = tiled_sdpa_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), dout.data_ptr(),
                             lse.data_ptr(), grads[0].data_ptr(), grads[1].data_ptr(), grads[2].data_ptr(),
                             B, H, S, D, math.nan if scale is None else scale, dtype,
@@ -276,8 +300,8 @@ def sdpa(q, k, v, causal: bool = False, scale=None, *, return_lse: bool = False,
         if lse.shape != (B, H, S) or lse.dtype != torch.float32 or not lse.is_contiguous():
             raise ValueError("lse_out must be contiguous float32 [B, H, S]")
     tm, tn = tile if tile is not None else (0, 0)
-    with torch.cuda.device(q.device):
-        stream = torch.cuda.current_stream().cuda_stream
+    guard, stream = _guard_and_stream(torch, q.device)
+    with guard:
         st = tiled_sdpa_fwd_ex(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
                                lse.data_ptr() if lse is not None else None,
                                B, H, S, D, math.nan if scale is None else scale, dtype, stream,
