@@ -147,6 +147,36 @@ def time_batched(pkg, torch, name, dtype, n, warmup, rotate=1):
     return w, a.elapsed_time(b) / n
 
 
+def time_graph_replay(pkg, torch, name, dtype, per_graph=20, replays=20):
+    """Per-launch time of `per_graph` launches recorded once into a HIP graph and replayed: the rate of
+    the kernel itself where the eager loop is bound by host time per call (C1)."""
+    from paper_2603_01960_amd.workloads import make_workload
+    w, q, k, v = make_workload(name, dtype)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    o = torch.empty_like(qd)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            pkg.sdpa(qd, kd, vd, out=o)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for _ in range(per_graph):
+            pkg.sdpa(qd, kd, vd, out=o)
+    for _ in range(3):
+        graph.replay()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(replays):
+        graph.replay()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / (replays * per_graph)
+
+
 def hbm_copy_ceiling(torch, mib=1024, steps=10):
     """GB/s (read + write) of a plain device-to-device copy too large for any cache: what a pure
     stream sustains on this GPU right now, next to the published 8 TB/s."""
@@ -412,6 +442,11 @@ def main():
                     "ms_per_launch_back_to_back": round(ms, 5),
                     "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
                     "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
+                if ms < 0.1:
+                    gms = time_graph_replay(pkg, torch, name, dt)
+                    others[f"{name}_{dt}"]["hip_graph_replay"] = {
+                        "ms_per_launch": round(gms, 5), "tflops": round(ww.flops / (gms * 1e-3) / 1e12, 2),
+                        "compulsory_GBs": round(ww.compulsory_bytes(2) / (gms * 1e-3) / 1e9, 1)}
                 sets = -(-(1 << 30) // int(ww.compulsory_bytes(2)))      # >= 1 GiB of distinct tensors in rotation
                 if 1 < sets <= 64:
                     _, ms = time_batched(pkg, torch, name, dt, max(4 * sets, args.steps), args.warmup, rotate=sets)
