@@ -52,6 +52,8 @@ def parse_args():
     ap.add_argument("--kv", default=None,
                     help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
     ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="with --kv: key/value heads (grouped heads: H query heads share H/kv-heads of them; 0 = H)")
     ap.add_argument("--bwd", action="store_true",
                     help="time the backward pass (tiled_sdpa_bwd: statistics, dV, dK and dQ kernels) of the workload")
     ap.add_argument("--tile", default=None, help="TM,TN to pin the schedule (default: heuristic)")
@@ -238,10 +240,13 @@ def bench_kv(pkg, torch, args, tile, flags):
     B, H, Sq, Skv, D = (int(x) for x in args.kv.split(","))
     dtype = args.dtype or "bf16"
     code = pkg.F16 if dtype == "f16" else pkg.BF16
+    Hkv = args.kv_heads or H
+    G = H // Hkv
     q = make_qkv(B, H, Sq, D, dtype, seed=4242)[0].cuda()
-    _, k, v = (t.cuda() for t in make_qkv(B, H, Skv, D, dtype, seed=4243))
-    splits = args.splits or pkg.kv_default_splits(B, H, Sq, Skv, D, code, flags)
-    ws = torch.empty(max(16, pkg.kv_workspace_bytes(B, H, Sq, D, splits)), dtype=torch.uint8, device="cuda")
+    _, k, v = (t.cuda() for t in make_qkv(B, Hkv, Skv, D, dtype, seed=4243))
+    # grouped heads run as Hkv heads of G*Sq query rows each (see binding.sdpa_kv)
+    splits = args.splits or pkg.kv_default_splits(B, Hkv, G * Sq, Skv, D, code, flags if G == 1 else flags & ~pkg.binding.FLAG_CAUSAL)
+    ws = torch.empty(max(16, pkg.kv_workspace_bytes(B, Hkv, G * Sq, D, splits)), dtype=torch.uint8, device="cuda")
     o = torch.empty_like(q)
     run = lambda: pkg.sdpa_kv(q, k, v, splits=splits, out=o, workspace=ws, tile=tile, flags=flags)
     for _ in range(args.warmup):
@@ -260,7 +265,7 @@ def bench_kv(pkg, torch, args, tile, flags):
     causal = bool(flags & pkg.binding.FLAG_CAUSAL)
     pairs = Sq * Skv - (Sq * (Sq - 1) // 2 if causal else 0)        # (query, key) pairs that contribute
     flops = 4.0 * B * H * pairs * D
-    comp_bytes = 2.0 * B * H * D * (2 * Skv + 2 * Sq)
+    comp_bytes = 2.0 * B * D * (2 * Hkv * Skv + 2 * H * Sq)
     ridge = PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
     if flops / comp_bytes >= ridge:
         tf = flops / (ms * 1e-3) / 1e12
@@ -277,9 +282,9 @@ def bench_kv(pkg, torch, args, tile, flags):
         "metric": "SDPA forward TFLOP/s (4*B*H*pairs*D / t)", "value": round(flops / (wall_ms * 1e-3) / 1e12, 3),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"KV: SDPA fwd {'causal' if causal else 'non-causal'} B={B} H={H} Sq={Sq} Skv={Skv} D={D} {dtype}",
+        "config": {"workload": f"KV: SDPA fwd {'causal' if causal else 'non-causal'} B={B} H={H}{'' if G == 1 else f' (kv heads {Hkv})'} Sq={Sq} Skv={Skv} D={D} {dtype}",
                    "splits": splits, "tile": list(tile) if tile else "heuristic",
-                   "cache_tokens_per_s": round(B * H * Skv / (ms * 1e-3), 1)},
+                   "cache_tokens_per_s": round(B * Hkv * Skv / (ms * 1e-3), 1)},
         "roofline": roofline}), flush=True)
 
 

@@ -120,6 +120,12 @@ int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flag
  *              are unspecified.  More splits than there are K/V tiles are allowed (the surplus ones
  *              contribute nothing) but waste workspace.
  *
+ * Grouped heads (G query heads reading one key/value head, the G heads of a group adjacent in q)
+ * need no entry point of their own where no row needs a limit of its own, i.e. without the causal
+ * flag or for a decoding step (Sq = 1, which sees the whole cache): q [B, G*Hkv, Sq, D] is the same
+ * memory as [B, Hkv, G*Sq, D], so the caller passes H = Hkv and Sq = G*Sq without the causal flag, and
+ * the keys of a group are read once for its G*Sq rows instead of G times.
+ *
  * Skv = 0 with Sq > 0 is TSDPA_ERR_BAD_SHAPE (a softmax over no keys).  Validation order: dtype, D,
  * shape, empty problem (B*H*Sq == 0), null pointers, alignment, tile, scale, splits, workspace, launch.
  */

@@ -174,6 +174,13 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
     split over ``splits`` workgroups per query tile (0 = heuristic).  Under ``causal`` the queries are
     the last Sq positions of the sequence.  ``workspace`` (any contiguous device tensor of enough bytes)
     is allocated through torch when not given and needed.
+
+    Grouped heads: k, v may be [B, Hkv, Skv, D] with H = G * Hkv, query head h reading key/value head
+    h // G.  The G query heads of a group are contiguous, so the call is the same entry point on the
+    view q [B, Hkv, G * Sq, D] (argument marshalling only): the G * Sq rows of a group share one pass
+    over its keys, which are read once instead of G times.  Without a mask every row sees every key, so
+    this holds for any Sq; under ``causal`` it holds for a decoding step (Sq = 1, the query sees the whole
+    cache) and is refused for Sq > 1, where the rows of a group would need different limits.
     """
     import torch
 
@@ -186,18 +193,26 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
             raise ValueError(f"{name} must be contiguous [B, H, S, D]")
     if q.dtype not in (torch.float16, torch.bfloat16) or k.dtype != q.dtype or v.dtype != q.dtype:
         raise ValueError("q, k, v must share dtype float16 or bfloat16")
-    if k.shape != v.shape or q.shape[:2] != k.shape[:2] or q.shape[3] != k.shape[3]:
-        raise ValueError("q must be [B, H, Sq, D] and k, v [B, H, Skv, D]")
+    if k.shape != v.shape or q.shape[0] != k.shape[0] or q.shape[3] != k.shape[3]:
+        raise ValueError("q must be [B, H, Sq, D] and k, v [B, Hkv, Skv, D]")
+    if k.shape[1] == 0 or q.shape[1] % k.shape[1] != 0:
+        raise ValueError("the number of query heads must be a multiple of the number of key/value heads")
     if k.device != q.device or v.device != q.device:
         raise ValueError("q, k, v must be on one device")
+    out_shape, group = q.shape, q.shape[1] // k.shape[1]
+    if group > 1:
+        if (flags & FLAG_CAUSAL) and q.shape[2] > 1:
+            raise ValueError("grouped heads under the causal mask are supported for Sq = 1 only")
+        flags &= ~FLAG_CAUSAL               # a single query at the end of the sequence sees every key
+        q = q.view(q.shape[0], k.shape[1], group * q.shape[2], q.shape[3])
     B, H, Sq, D = q.shape
     Skv = k.shape[2]
     dtype = F16 if q.dtype == torch.float16 else BF16
     if out is None:
-        out = torch.empty_like(q)
-    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
+        out = torch.empty(out_shape, dtype=q.dtype, device=q.device)
+    elif out.shape != out_shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
         raise ValueError("out must match q in shape, dtype, device and be contiguous")
-    lse = torch.empty((B, H, Sq), dtype=torch.float32, device=q.device) if return_lse else None
+    lse = torch.empty(out_shape[:3], dtype=torch.float32, device=q.device) if return_lse else None
     tm, tn = tile if tile is not None else (0, 0)
     n = splits if splits else kv_default_splits(B, H, Sq, Skv, D, dtype, flags)
     need = kv_workspace_bytes(B, H, Sq, D, n)

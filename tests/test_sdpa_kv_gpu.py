@@ -182,3 +182,37 @@ def test_long_cache_decode_full_size(dtype):
     rows = sample_rows(8192, limit=24)
     check_kv(q, k, v, dtype, rows=rows, tag="few heads, long sequence")
     check_kv(q, k, v, dtype, rows=rows, causal=True, tag="few heads, long sequence, causal")
+
+
+# ------------------------------------------------------------------ grouped heads (several query heads per key/value head)
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,H,Hkv,Sq,Skv,D,causal,splits", [
+    (2, 8, 2, 1, 1000, 128, False, 0), (2, 8, 2, 1, 1000, 128, True, 0), (1, 32, 4, 1, 4096, 128, True, 8),
+    (1, 12, 3, 5, 333, 64, False, 3), (1, 8, 8, 1, 257, 64, True, 0), (1, 16, 1, 7, 2048, 96, False, 0),
+])
+def test_grouped_heads_share_one_pass_over_their_keys(dtype, B, H, Hkv, Sq, Skv, D, causal, splits):
+    """Query head h reads key/value head h // G.  The oracle gets K and V repeated G times along the
+    head axis, i.e. the plain definition for every query head."""
+    G = H // Hkv
+    q = make_qkv(B, H, Sq, D, dtype, seed=71)[0]
+    _, k, v = make_qkv(B, Hkv, Skv, D, dtype, seed=72)
+    say(f"[case] grouped heads B={B} H={H} Hkv={Hkv} Sq={Sq} Skv={Skv} D={D} {dtype} causal={causal} splits={splits}")
+    o, lse = binding.sdpa_kv(q.cuda(), k.cuda(), v.cuda(), causal=causal, splits=splits, return_lse=True)
+    torch.cuda.synchronize()
+    assert o.shape == q.shape and lse.shape == q.shape[:3]
+    kx = np.repeat(k.float().numpy(), G, axis=1)
+    vx = np.repeat(v.float().numpy(), G, axis=1)
+    ref_o, ref_lse = orc.sdpa(q.float().numpy(), kx, vx, return_lse=True, causal=causal)
+    err = float(np.abs(o.cpu().double().numpy() - ref_o).max())
+    lerr = float(np.abs(lse.cpu().double().numpy() - ref_lse).max())
+    say(f"        max|dO|={err:.3e} max|dLSE|={lerr:.3e}")
+    assert err <= TOL[dtype] and lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16)
+
+
+def test_grouped_heads_are_refused_where_rows_would_need_different_limits():
+    q = make_qkv(1, 8, 4, 64, "f16", seed=73)[0].cuda()
+    _, k, v = (t.cuda() for t in make_qkv(1, 2, 64, 64, "f16", seed=74))
+    with pytest.raises(ValueError):
+        binding.sdpa_kv(q, k, v, causal=True)
+    with pytest.raises(ValueError):
+        binding.sdpa_kv(q[:, :7].contiguous(), k, v)       # 7 query heads over 2 key/value heads
