@@ -120,12 +120,6 @@ int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flag
  *              are unspecified.  More splits than there are K/V tiles are allowed (the surplus ones
  *              contribute nothing) but waste workspace.
  *
- * Grouped heads (G query heads reading one key/value head, the G heads of a group adjacent in q)
- * need no entry point of their own where no row needs a limit of its own, i.e. without the causal
- * flag or for a decoding step (Sq = 1, which sees the whole cache): q [B, G*Hkv, Sq, D] is the same
- * memory as [B, Hkv, G*Sq, D], so the caller passes H = Hkv and Sq = G*Sq without the causal flag, and
- * the keys of a group are read once for its G*Sq rows instead of G times.
- *
  * Skv = 0 with Sq > 0 is TSDPA_ERR_BAD_SHAPE (a softmax over no keys).  Validation order: dtype, D,
  * shape, empty problem (B*H*Sq == 0), null pointers, alignment, tile, scale, splits, workspace, launch.
  */
@@ -133,6 +127,29 @@ int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, floa
                       int B, int H, int Sq, int Skv, int D, float scale, int dtype, void *stream,
                       int tile_m, int tile_n, unsigned flags,
                       int splits, void *workspace, unsigned long long workspace_bytes);
+
+/*
+ * tiled_sdpa_fwd_kv with grouped heads: H query heads read Hkv key/value heads, query head h the
+ * key/value head h / (H / Hkv) -- the layout of multi-query and grouped-query KV caches.  The paper
+ * has one key/value head per query head (Section 3.1); per query head this computes the same Eq. 1,
+ * with the causal limit of tiled_sdpa_fwd_kv for each head's Sq rows.
+ *
+ *   q, o : [B, H, Sq, D];  lse : NULL or FP32 [B, H, Sq];  k, v : [B, Hkv, Skv, D];  H % Hkv == 0.
+ *   Everything else as for tiled_sdpa_fwd_kv, which is this call with Hkv = H.  The heuristics see
+ *   B * Hkv heads of (H / Hkv) * Sq rows each: tiled_sdpa_kv_default_splits(B, Hkv, (H / Hkv) * Sq, ...)
+ *   without the causal flag reports the split count used for splits = 0, and the workspace size is
+ *   tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, n).
+ *
+ * The query heads of a group are adjacent in memory, so a group's (H / Hkv) * Sq rows form one run of
+ * rows that streams the group's keys and values once (instead of once per query head): on a
+ * decoding step the otherwise empty rows of the 32-row MFMA tile carry the other heads of the
+ * group.  Hkv <= 0 with H > 0, or H not a multiple of Hkv, is TSDPA_ERR_BAD_SHAPE (checked right
+ * after the shape checks of tiled_sdpa_fwd_kv).
+ */
+int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, float *lse,
+                       int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                       int tile_m, int tile_n, unsigned flags,
+                       int splits, void *workspace, unsigned long long workspace_bytes);
 
 /* Splits the heuristic picks (1 when the query tiles alone fill the GPU); returns a status code. */
 int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags, int *splits);

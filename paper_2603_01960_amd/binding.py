@@ -26,6 +26,7 @@ EXPORTS = (
     "tiled_sdpa_bwd_workspace_bytes",
     "tiled_sdpa_default_tile",
     "tiled_sdpa_fwd_kv",
+    "tiled_sdpa_fwd_gqa",
     "tiled_sdpa_kv_default_splits",
     "tiled_sdpa_kv_workspace_bytes",
     "tiled_sdpa_probe_mfma",
@@ -69,6 +70,8 @@ def load_library():
     lib.tiled_sdpa_kv_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_kv_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     lib.tiled_sdpa_bwd.restype = ci
+    lib.tiled_sdpa_fwd_gqa.restype = ci
+    lib.tiled_sdpa_fwd_gqa.argtypes = [vp] * 5 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
@@ -168,6 +171,13 @@ def tiled_sdpa_fwd_kv(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Sq, Skv, D, sca
                                                 splits, workspace_ptr, workspace_bytes))
 
 
+def tiled_sdpa_fwd_gqa(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Hkv, Sq, Skv, D, scale, dtype, stream,
+                       tile_m=0, tile_n=0, flags=0, splits=0, workspace_ptr=None, workspace_bytes=0) -> int:
+    return int(load_library().tiled_sdpa_fwd_gqa(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Hkv, Sq, Skv, D,
+                                                 float(scale), dtype, stream, tile_m, tile_n, flags,
+                                                 splits, workspace_ptr, workspace_bytes))
+
+
 def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, return_lse: bool = False,
             out=None, workspace=None, tile=None, flags: int = 0):
     """Attention of q [B, H, Sq, D] over k, v [B, H, Skv, D] (KV-cache / decoding shapes), the key range
@@ -176,11 +186,7 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
     is allocated through torch when not given and needed.
 
     Grouped heads: k, v may be [B, Hkv, Skv, D] with H = G * Hkv, query head h reading key/value head
-    h // G.  The G query heads of a group are contiguous, so the call is the same entry point on the
-    view q [B, Hkv, G * Sq, D] (argument marshalling only): the G * Sq rows of a group share one pass
-    over its keys, which are read once instead of G times.  Without a mask every row sees every key, so
-    this holds for any Sq; under ``causal`` it holds for a decoding step (Sq = 1, the query sees the whole
-    cache) and is refused for Sq > 1, where the rows of a group would need different limits.
+    h // G (tiled_sdpa_fwd_gqa): the rows of a group share one pass over its keys.
     """
     import torch
 
@@ -199,14 +205,10 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
         raise ValueError("the number of query heads must be a multiple of the number of key/value heads")
     if k.device != q.device or v.device != q.device:
         raise ValueError("q, k, v must be on one device")
-    out_shape, group = q.shape, q.shape[1] // k.shape[1]
-    if group > 1:
-        if (flags & FLAG_CAUSAL) and q.shape[2] > 1:
-            raise ValueError("grouped heads under the causal mask are supported for Sq = 1 only")
-        flags &= ~FLAG_CAUSAL               # a single query at the end of the sequence sees every key
-        q = q.view(q.shape[0], k.shape[1], group * q.shape[2], q.shape[3])
     B, H, Sq, D = q.shape
-    Skv = k.shape[2]
+    Hkv, Skv = k.shape[1], k.shape[2]
+    group = H // Hkv
+    out_shape = q.shape
     dtype = F16 if q.dtype == torch.float16 else BF16
     if out is None:
         out = torch.empty(out_shape, dtype=q.dtype, device=q.device)
@@ -214,7 +216,9 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
         raise ValueError("out must match q in shape, dtype, device and be contiguous")
     lse = torch.empty(out_shape[:3], dtype=torch.float32, device=q.device) if return_lse else None
     tm, tn = tile if tile is not None else (0, 0)
-    n = splits if splits else kv_default_splits(B, H, Sq, Skv, D, dtype, flags)
+    # the library's heuristics see B * Hkv heads of group * Sq rows each
+    n = splits if splits else kv_default_splits(B, Hkv, group * Sq, Skv, D, dtype,
+                                                flags if group == 1 else flags & ~FLAG_CAUSAL)
     need = kv_workspace_bytes(B, H, Sq, D, n)
     if workspace is None and need:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
@@ -222,10 +226,10 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     guard, stream = _guard_and_stream(torch, q.device)
     with guard:
-        st = tiled_sdpa_fwd_kv(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                               lse.data_ptr() if lse is not None else None,
-                               B, H, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
-                               tm, tn, flags, n, ws_ptr, ws_bytes)
+        st = tiled_sdpa_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                lse.data_ptr() if lse is not None else None,
+                                B, H, Hkv, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
+                                tm, tn, flags, n, ws_ptr, ws_bytes)
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return (out, lse) if return_lse else out

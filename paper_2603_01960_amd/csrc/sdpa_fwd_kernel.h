@@ -127,12 +127,16 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
 // contiguous runs of tiles, one workgroup each.  With splits > 1 a workgroup writes its unnormalised
 // state (o, m, l of Eqs. 2-4) to `ws` instead of O: o as float [BH][splits][S][D], followed by
 // (m, l) pairs as float [BH][splits][S][2]; sdpa_merge_kernel combines them.
+// Grouped heads (G query heads reading one key/value head) arrive folded: a "head" of the KV = true
+// kernel is one key/value head and its S = G * Sp rows are the Sp positions of each of the G query
+// heads in turn, so only the causal limit has to know Sp (`rows_per_head`; equal to S when nothing is
+// folded).
 template <typename T, int D, int NW, int TN, int WPS, bool KV>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
                 float tau, uint32_t qsign, int linear_grid, int causal,
-                int Skv_arg, int splits_arg, float *__restrict__ ws)
+                int Skv_arg, int splits_arg, float *__restrict__ ws, int rows_per_head)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     using E = Elem<T>;
@@ -155,7 +159,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 
     const int Skv = KV ? Skv_arg : S;             // key rows; S is the number of query rows
     const int splits = KV ? splits_arg : 1;
-    const int koff = Skv - S;                     // position of query row 0 in the key sequence (causal)
+    const int Sp = KV ? rows_per_head : S;        // query positions per query head (S = G * Sp rows when folded)
+    const bool folded = KV && Sp != S;
+    const int koff = Skv - Sp;                    // position of a head's query row 0 in the key sequence (causal)
     const int wg = remap_workgroup(blockIdx.x, N, linear_grid != 0);
     // query tile fastest, then split, then head: neighbours share one run of K/V tiles
     const int hs = wg / nQ;
@@ -185,9 +191,17 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const int nT = (Skv + TN - 1) / TN;
     const int r0 = qt * TM;
     const int last_row = (r0 + TM < S ? r0 + TM : S) - 1;
-    const int nTw = causal ? (last_row + koff) / TN + 1 : nT;
-    const int klim = causal ? (qrow < S ? qrow : S - 1) + koff : Skv - 1;
-    const int nfull = ((causal ? (r0 < S - 1 ? r0 : S - 1) + koff : Skv - 1) + 1) / TN;
+    // least and greatest position among the workgroup's rows, and this lane's own
+    int pos_lo = r0, pos_hi = last_row, pos_own = qrow_c;
+    if (folded) {
+        const int g0 = r0 / Sp, g1 = last_row / Sp;
+        if (g0 == g1) { pos_lo -= g0 * Sp; pos_hi -= g0 * Sp; }
+        else          { pos_lo = 0; pos_hi = Sp - 1; }        // the tile crosses into the next query head
+        pos_own = qrow_c % Sp;
+    }
+    const int nTw = causal ? (pos_hi + koff) / TN + 1 : nT;
+    const int klim = causal ? pos_own + koff : Skv - 1;
+    const int nfull = ((causal ? pos_lo + koff : Skv - 1) + 1) / TN;
     // this workgroup's run of tiles [t0, t1): all nTw of them unless the key range is split
     const int per_split = (nTw + splits - 1) / splits;
     const int t0 = KV ? sp * per_split : 0;

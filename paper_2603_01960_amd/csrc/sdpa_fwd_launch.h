@@ -19,6 +19,7 @@ struct LaunchArgs {
     int Skv;          // key/value rows per head (kv = 1)
     int splits;       // workgroups per (head, query tile) along the key axis (kv = 1); > 1 writes partials to ws
     float *ws;        // split workspace: float [BH][splits][S][D] then [BH][splits][S][2]
+    int rows_per_head; // kv = 1: query positions per query head; S / rows_per_head query heads are folded into the S rows
     hipStream_t stream;
 };
 

@@ -152,6 +152,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
     a.lse = lse;
     a.BH = B * H;
     a.S = S;
+    a.rows_per_head = S;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
@@ -200,20 +201,35 @@ int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, floa
                       int tile_m, int tile_n, unsigned flags,
                       int splits, void *workspace, unsigned long long workspace_bytes)
 {
+    return tiled_sdpa_fwd_gqa(q, k, v, o, lse, B, H, H, Sq, Skv, D, scale, dtype, stream, tile_m, tile_n, flags,
+                              splits, workspace, workspace_bytes);
+}
+
+int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, float *lse,
+                       int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                       int tile_m, int tile_n, unsigned flags,
+                       int splits, void *workspace, unsigned long long workspace_bytes)
+{
     int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
     if (st != TSDPA_OK) return st;
+    if (Hkv < 0 || (H > 0 && (Hkv == 0 || H % Hkv != 0))) return TSDPA_ERR_BAD_SHAPE;
     if ((int64_t)B * H * Sq == 0) return TSDPA_OK;
+    // the G query heads of a group are adjacent, so q, o and lse are also [B, Hkv, G*Sq, ...]: the
+    // kernel runs one "head" per key/value head over the G*Sq rows that read it
+    const int G = H / Hkv;
+    if ((int64_t)G * Sq > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
+    const int rows = G * Sq;
     if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o;
     if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     if (tile_m == 0 && tile_n == 0)
-        pick_tile_kv(Sq, Skv, D, &tile_m, &tile_n);
+        pick_tile_kv(rows, Skv, D, &tile_m, &tile_n);
     else if (!(tile_m == 64 || tile_m == 128) || !(tile_n == 32 || tile_n == 64))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
     if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
     if (splits < 0 || splits > TSDPA_MAX_SPLITS) return TSDPA_ERR_BAD_SPLITS;
-    if (splits == 0) splits = pick_splits(B * H, Sq, Skv, tile_m, tile_n);
+    if (splits == 0) splits = pick_splits(B * Hkv, rows, Skv, tile_m, tile_n);
     if (splits > 1) {
         if (!workspace || ((uintptr_t)workspace & 15u) != 0 ||
             workspace_bytes < tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits))
@@ -226,8 +242,9 @@ int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, floa
     a.v = v;
     a.o = o;
     a.lse = lse;
-    a.BH = B * H;
-    a.S = Sq;
+    a.BH = B * Hkv;
+    a.S = rows;
+    a.rows_per_head = Sq;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
@@ -261,10 +278,10 @@ int tiled_sdpa_fwd_kv(const void *q, const void *k, const void *v, void *o, floa
         const unsigned blocks = (unsigned)((threads + 255) / 256);
         if (dtype == TSDPA_F16)
             hipLaunchKernelGGL(tsdpa::sdpa_merge_kernel<_Float16>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                               (const float *)workspace, (_Float16 *)o, lse, B * H, Sq, D, splits);
+                               (const float *)workspace, (_Float16 *)o, lse, B * Hkv, rows, D, splits);
         else
             hipLaunchKernelGGL(tsdpa::sdpa_merge_kernel<__bf16>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,
-                               (const float *)workspace, (__bf16 *)o, lse, B * H, Sq, D, splits);
+                               (const float *)workspace, (__bf16 *)o, lse, B * Hkv, rows, D, splits);
         if (hipGetLastError() != hipSuccess) return TSDPA_ERR_LAUNCH;
     }
     return TSDPA_OK;

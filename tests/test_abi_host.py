@@ -133,6 +133,28 @@ def test_kv_entry_point_validation_order_and_codes(lib, kwargs, expect):
     assert st == expect, binding.status_string(st)
 
 
+@pytest.mark.parametrize("kwargs,expect", [
+    (dict(), NULL),                                 # q = None below: everything before the pointers passes
+    (dict(Hkv=3), SHAPE),                           # 8 query heads over 3 key/value heads
+    (dict(Hkv=0), SHAPE),
+    (dict(Hkv=-2), SHAPE),
+    (dict(Hkv=16), SHAPE),                          # more key/value heads than query heads
+    (dict(H=0, Hkv=0), OK),                         # empty problem
+    (dict(Hkv=8), NULL),                            # Hkv = H is tiled_sdpa_fwd_kv
+    (dict(Hkv=1), NULL),                            # multi-query
+    (dict(D=80, Hkv=3), BAD_D),                     # head dim is checked before the grouping
+    (dict(Sq=800, flags=binding.FLAG_CAUSAL), SHAPE),   # causal needs Skv >= Sq per query head ...
+    (dict(Sq=350, flags=binding.FLAG_CAUSAL), NULL),    # ... not per folded group of 4 * 350 rows
+    (dict(B=1 << 12, H=1 << 12, Hkv=1, Sq=1 << 9), SHAPE),
+])
+def test_gqa_entry_point_validation(lib, kwargs, expect):
+    a = dict(B=2, H=8, Hkv=2, Sq=5, Skv=700, D=64, flags=0)
+    a.update(kwargs)
+    st = binding.tiled_sdpa_fwd_gqa(None, P, P, P, None, a["B"], a["H"], a["Hkv"], a["Sq"], a["Skv"], a["D"],
+                                    0.125, 1, None, 0, 0, a["flags"], 1, None, 0)
+    assert st == expect, binding.status_string(st)
+
+
 def test_kv_workspace_size_and_default_splits(lib):
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 1) == 0
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 0) == 0

@@ -209,10 +209,55 @@ def test_grouped_heads_share_one_pass_over_their_keys(dtype, B, H, Hkv, Sq, Skv,
     assert err <= TOL[dtype] and lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16)
 
 
-def test_grouped_heads_are_refused_where_rows_would_need_different_limits():
-    q = make_qkv(1, 8, 4, 64, "f16", seed=73)[0].cuda()
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("tile", [None, (64, 32), (128, 64)])
+@pytest.mark.parametrize("B,H,Hkv,Sq,Skv,D,splits", [
+    (1, 8, 2, 40, 200, 64, 0),        # four heads of 40 rows in one 160-row run: tiles cross head boundaries
+    (2, 6, 3, 64, 64, 128, 0),        # square per head (prefill from an empty cache), two heads per group
+    (1, 4, 1, 130, 1000, 128, 3),     # multi-query, a prefill chunk after 870 cached positions, split keys
+    (1, 16, 2, 7, 7, 64, 0),          # groups of eight tiny heads inside one tile
+    (1, 4, 2, 200, 333, 96, 2),
+    (1, 3, 1, 33, 4096, 128, 0),      # split heuristic on a long cache
+])
+def test_grouped_heads_under_the_causal_mask(dtype, tile, B, H, Hkv, Sq, Skv, D, splits):
+    """Every query head keeps its own causal limit (its rows are the last Sq positions) although the
+    rows of a group run through the kernel as one block."""
+    G = H // Hkv
+    q = make_qkv(B, H, Sq, D, dtype, seed=75)[0]
+    _, k, v = make_qkv(B, Hkv, Skv, D, dtype, seed=76)
+    say(f"[case] grouped causal B={B} H={H} Hkv={Hkv} Sq={Sq} Skv={Skv} D={D} {dtype} tile={tile} splits={splits}")
+    o, lse = binding.sdpa_kv(q.cuda(), k.cuda(), v.cuda(), causal=True, splits=splits, tile=tile, return_lse=True)
+    torch.cuda.synchronize()
+    kx = np.repeat(k.float().numpy(), G, axis=1)
+    vx = np.repeat(v.float().numpy(), G, axis=1)
+    ref_o, ref_lse = orc.sdpa(q.float().numpy(), kx, vx, return_lse=True, causal=True)
+    err = float(np.abs(o.cpu().double().numpy() - ref_o).max())
+    lerr = float(np.abs(lse.cpu().double().numpy() - ref_lse).max())
+    say(f"        max|dO|={err:.3e} max|dLSE|={lerr:.3e}")
+    assert torch.isfinite(o.float()).all()
+    assert err <= TOL[dtype] and lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16)
+
+
+def test_grouped_heads_do_not_see_later_keys():
+    """Changing keys and values after a head's last position changes nothing for it: with Sq = 3 rows per
+    head at the end of 50 keys, row i of every head of the group must ignore keys > 47 + i."""
+    q = make_qkv(1, 4, 3, 64, "f16", seed=77)[0].cuda()
+    _, k, v = (t.cuda() for t in make_qkv(1, 1, 50, 64, "f16", seed=78))
+    o1 = binding.sdpa_kv(q, k, v, causal=True)
+    k2, v2 = k.clone(), v.clone()
+    k2[:, :, 48:] = 9.0
+    v2[:, :, 48:] = -7.0
+    o2 = binding.sdpa_kv(q, k2, v2, causal=True)
+    torch.cuda.synchronize()
+    assert torch.equal(o1[:, :, 0], o2[:, :, 0])          # row 0 of every head sees keys 0..47 only
+    assert not torch.equal(o1[:, :, 2], o2[:, :, 2])      # row 2 sees them all
+
+
+def test_head_counts_that_do_not_divide_are_refused():
+    q = make_qkv(1, 7, 4, 64, "f16", seed=73)[0].cuda()
     _, k, v = (t.cuda() for t in make_qkv(1, 2, 64, 64, "f16", seed=74))
     with pytest.raises(ValueError):
-        binding.sdpa_kv(q, k, v, causal=True)
-    with pytest.raises(ValueError):
-        binding.sdpa_kv(q[:, :7].contiguous(), k, v)       # 7 query heads over 2 key/value heads
+        binding.sdpa_kv(q, k, v)                          # 7 query heads over 2 key/value heads
+    st = binding.tiled_sdpa_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), q.data_ptr(), None,
+                                    1, 7, 2, 4, 64, 64, 0.125, binding.F16, None)
+    assert st == 2
