@@ -11,11 +11,13 @@ namespace tsdpa {
 // the dQ / dK / dV pass, and the wavefronts per SIMD the register budget of each is sized for.  At D = 128 the
 // dK pass (two resident operand sets, one output, per-row statistics) is the tightest on registers
 // and runs best on 32-row tiles.
+// FUSED_DKV: dK and dV in one keys-resident pass (seven S x S x D products per call instead of eight,
+// one launch fewer); its two accumulators and two resident operand sets fit 256 registers at D = 64.
 template <int D> struct BwdShape;
-template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 64, 64}; };
-template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 32, 64}; };
-template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {64, 32, 64}; };
-template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[3] = {2, 2, 2}, TS[3] = {32, 32, 32}; };   // 512-byte LDS rows
+template <> struct BwdShape<64>  { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {64, 64, 64, 64}; static constexpr bool FUSED_DKV = true; };
+template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {64, 32, 64, 32}; static constexpr bool FUSED_DKV = false; };
+template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {64, 32, 64, 32}; static constexpr bool FUSED_DKV = false; };
+template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {32, 32, 32, 32}; static constexpr bool FUSED_DKV = false; };   // 512-byte LDS rows
 
 template <typename T, int D, int MODE>
 int launch_bwd_pass(const BwdLaunchArgs &a)
@@ -32,10 +34,10 @@ int launch_bwd_pass(const BwdLaunchArgs &a)
     if (attr_err != hipSuccess) return (int)attr_err;
     const int nR = (a.S + NW * 32 - 1) / (NW * 32);
     const int N = a.BH * nR;
-    void *out = MODE == BWD_DQ ? a.dq : (MODE == BWD_DK ? a.dk : a.dv);
+    void *out = MODE == BWD_DQ ? a.dq : (MODE == BWD_DV ? a.dv : a.dk);
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.delta,
-                       (T *)out, a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes);
+                       (T *)out, (T *)(MODE == BWD_DKV ? a.dv : nullptr), a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes);
     return (int)hipGetLastError();
 }
 
@@ -48,9 +50,13 @@ int launch_bwd(const BwdLaunchArgs &a)
                        (const T *)a.o, (const T *)a.dout, a.lse, a.delta, a.lse2, rows);
     int err = (int)hipGetLastError();
     if (err != 0) return err;
-    err = launch_bwd_pass<T, D, BWD_DV>(a);
-    if (err != 0) return err;
-    err = launch_bwd_pass<T, D, BWD_DK>(a);
+    if constexpr (BwdShape<D>::FUSED_DKV) {
+        err = launch_bwd_pass<T, D, BWD_DKV>(a);
+    } else {
+        err = launch_bwd_pass<T, D, BWD_DV>(a);
+        if (err != 0) return err;
+        err = launch_bwd_pass<T, D, BWD_DK>(a);
+    }
     if (err != 0) return err;
     return launch_bwd_pass<T, D, BWD_DQ>(a);
 }

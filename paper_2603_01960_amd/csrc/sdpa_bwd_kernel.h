@@ -86,13 +86,16 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 #endif
 }
 
-enum { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2 };
+// BWD_DKV is the dK and dV passes in one (scores and P computed once for both): two output
+// accumulators and both resident operand sets, which fits 256 registers per lane at D = 64 only.
+enum { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2, BWD_DKV = 3 };
 
 template <typename T, int D, int NW, int TS, int WPS, int MODE>
 __global__ void __launch_bounds__(NW * 64, WPS)
 sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 const T *__restrict__ dout, const float *__restrict__ stats,   // Delta [B*H*S + slack], then LSE likewise
                 T *__restrict__ out,   // dQ, dK or dV
+                T *__restrict__ out2,  // dV of the fused dK + dV pass, else unused
                 int S, int nR, int N, float c, float scale, uint32_t rsign, int causal, unsigned stat_bytes)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
@@ -102,6 +105,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using G = BwdGeom<D, TS>;
     constexpr bool KEYS_RES = MODE != BWD_DQ;
     constexpr bool NEED_DP = MODE != BWD_DV;      // dP product and Delta
+    constexpr bool FUSED = MODE == BWD_DKV;       // P kept next to dS, second accumulator for dV
     constexpr int RM = NW * 32;                   // resident rows per workgroup
     constexpr int CPR = G::DG / 8;                // 16-byte chunks per LDS row
     constexpr int GCPR = D / 8;                   // ... of which this many hold data
@@ -200,11 +204,14 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         }
     };
 
-    f32x16 oacc[DB];
+    f32x16 oacc[DB], oacc2[FUSED ? DB : 1];
 #pragma unroll
     for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
+        for (int i = 0; i < 16; ++i) {
+            oacc[db][i] = 0.f;
+            if constexpr (FUSED) oacc2[db][i] = 0.f;
+        }
 
     // ---- per-lane LDS read pointers (tile slot, nb, ks enter as immediate offsets)
     // row-wise: row l32 (+32*nb), chunk (2*kk + g) ^ swz(row)
@@ -258,7 +265,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 
     // One streamed tile: P (and dS) from the first products, rounded to 16 bits as B-operands of the
     // second product.  The next tile's loads are issued first and land while this one is computed.
-    vec8 xb[NB][2];
+    vec8 xb[NB][2], pb[FUSED ? NB : 1][2];
     auto tile = [&](int j, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
         constexpr bool MASK = decltype(mask_tag)::value;
@@ -288,20 +295,22 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                     const int i = r4 * 4 + e;
                     const float l2 = KEYS_RES ? st_lse[e] : lse_r;
                     float x = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[i], c, -l2));        // P
-                    if constexpr (NEED_DP) {
-                        const float dl = KEYS_RES ? st_delta[e] : delta_r;
-                        x *= dpacc[i] - dl;                                                   // dS
-                    }
                     if constexpr (MASK) {
                         const int trow = trow0 + nb * 32 + r4 * 8 + e;
                         if (trow < tlo || trow > thi) x = 0.f;
                     }
+                    if constexpr (FUSED) pb[nb][i >> 3][i & 7] = (T)x;
+                    if constexpr (NEED_DP) {
+                        const float dl = KEYS_RES ? st_delta[e] : delta_r;
+                        x *= dpacc[i] - dl;                                                   // dS
+                    }
                     xb[nb][i >> 3][i & 7] = (T)x;
                 }
-                if constexpr (MODE == BWD_DK) __builtin_amdgcn_sched_barrier(0);
+                if constexpr (MODE == BWD_DK || FUSED) __builtin_amdgcn_sched_barrier(0);
             }
         }
         accumulate(MODE == BWD_DV ? T2BASE + cur : cur, xb, oacc);
+        if constexpr (FUSED) accumulate(T2BASE + cur, pb, oacc2);       // dV^T += dO^T P
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
@@ -363,6 +372,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     static_assert(NW * 32 * G::ROW <= G::LDS_BYTES, "output staging does not fit the LDS");
     store(oacc, MODE == BWD_DV ? 1.0f : scale, out);
+    if constexpr (FUSED) store(oacc2, 1.0f, out2);   // same staging region: it is private to the wavefront, whose LDS operations complete in order
 #endif
 }
 
