@@ -331,9 +331,11 @@ def bench_bwd(pkg, torch, args, flags):
         "config": {"workload": f"{w.name}: SDPA bwd {'causal' if causal else 'non-causal'} B={w.B} H={w.H} S={w.S} D={w.D} {dtype}"},
         "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf / PEAK_MFMA_TFLOPS, 4), "traffic": None,
-                     "kernel": "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dV> + sdpa_bwd_kernel<dK> + sdpa_bwd_kernel<dQ>",
+                     "kernel": ("sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dK+dV> + sdpa_bwd_kernel<dQ>" if w.D == 64 else
+                                "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dV> + sdpa_bwd_kernel<dK> + sdpa_bwd_kernel<dQ>"),
                      "ms_avg_all_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
-                     "executed_mfma_flops_per_launch": flops * 8.0 / 5.0}}), flush=True)
+                     # scores and dP are recomputed per pass: 7 products with the fused dK + dV pass of D = 64, else 8
+                     "executed_mfma_flops_per_launch": flops * (7.0 if w.D == 64 else 8.0) / 5.0}}), flush=True)
 
 
 def cpu_baseline(w, q, k, v, target_seconds):
