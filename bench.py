@@ -52,6 +52,9 @@ def parse_args():
     ap.add_argument("--kv", default=None,
                     help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
     ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
+    ap.add_argument("--kv-fill", type=float, default=0.0,
+                    help="with --kv: treat Skv as the capacity of a cache filled to this fraction in every batch entry "
+                         "(tiled_sdpa_fwd_kvcache with a length per entry); 0 = a full cache without lengths")
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="with --kv: key/value heads (grouped heads: H query heads share H/kv-heads of them; 0 = H)")
     ap.add_argument("--bwd", action="store_true",
@@ -248,7 +251,11 @@ def bench_kv(pkg, torch, args, tile, flags):
     splits = args.splits or pkg.kv_default_splits(B, Hkv, G * Sq, Skv, D, code, flags if G == 1 else flags & ~pkg.binding.FLAG_CAUSAL)
     ws = torch.empty(max(16, pkg.kv_workspace_bytes(B, Hkv, G * Sq, D, splits)), dtype=torch.uint8, device="cuda")
     o = torch.empty_like(q)
-    run = lambda: pkg.sdpa_kv(q, k, v, splits=splits, out=o, workspace=ws, tile=tile, flags=flags)
+    cap, lens = Skv, None
+    if args.kv_fill > 0:
+        Skv = max(1, int(round(cap * min(1.0, args.kv_fill))))          # valid rows per entry: what is read and computed
+        lens = torch.full((B,), Skv, dtype=torch.int32, device="cuda")
+    run = lambda: pkg.sdpa_kv(q, k, v, splits=splits, out=o, workspace=ws, tile=tile, flags=flags, kv_lens=lens)
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
@@ -283,7 +290,7 @@ def bench_kv(pkg, torch, args, tile, flags):
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"KV: SDPA fwd {'causal' if causal else 'non-causal'} B={B} H={H}{'' if G == 1 else f' (kv heads {Hkv})'} Sq={Sq} Skv={Skv} D={D} {dtype}",
-                   "splits": splits, "tile": list(tile) if tile else "heuristic",
+                   "cache_capacity": cap, "splits": splits, "tile": list(tile) if tile else "heuristic",
                    "cache_tokens_per_s": round(B * Hkv * Skv / (ms * 1e-3), 1)},
         "roofline": roofline}), flush=True)
 

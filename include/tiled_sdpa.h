@@ -151,6 +151,30 @@ int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, flo
                        int tile_m, int tile_n, unsigned flags,
                        int splits, void *workspace, unsigned long long workspace_bytes);
 
+/*
+ * tiled_sdpa_fwd_gqa over a KV cache whose batch entries are filled to different lengths (the
+ * serving form of the KV-cache variants the paper names as future work, Section 8): k and v are
+ * [B, Hkv, Skv, D] with Skv the CAPACITY of the cache, and batch entry b holds kv_lens[b] valid key
+ * rows at the front of each of its heads.
+ *
+ *   kv_lens : device pointer to B 32-bit integers, 4-byte aligned, read by the kernels when they run
+ *             (not by this call); values are clamped to [0, Skv].  NULL = every entry holds Skv rows,
+ *             which is tiled_sdpa_fwd_gqa.
+ *
+ * Entry b is computed as tiled_sdpa_fwd_gqa would compute it on its first kv_lens[b] key rows: rows
+ * past the length are never fetched, and under TSDPA_FLAG_CAUSAL the Sq queries are the last Sq
+ * positions of the kv_lens[b]-long sequence (key j contributes to query row i only if
+ * j <= i + kv_lens[b] - Sq).  A query row that no key reaches -- an empty entry, or under the causal
+ * flag an entry shorter than Sq for its first Sq - kv_lens[b] rows -- gets O = 0 and LSE = -infinity
+ * (a softmax over no keys has no value; zero is what leaves a residual stream untouched).  Shapes are
+ * validated against the capacity; the split heuristic sees the capacity too, so workspace sizes do not
+ * depend on the lengths.  Everything else as for tiled_sdpa_fwd_gqa.
+ */
+int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o, float *lse, const int *kv_lens,
+                           int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                           int tile_m, int tile_n, unsigned flags,
+                           int splits, void *workspace, unsigned long long workspace_bytes);
+
 /* Splits the heuristic picks (1 when the query tiles alone fill the GPU); returns a status code. */
 int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags, int *splits);
 

@@ -27,6 +27,7 @@ EXPORTS = (
     "tiled_sdpa_default_tile",
     "tiled_sdpa_fwd_kv",
     "tiled_sdpa_fwd_gqa",
+    "tiled_sdpa_fwd_kvcache",
     "tiled_sdpa_kv_default_splits",
     "tiled_sdpa_kv_workspace_bytes",
     "tiled_sdpa_probe_mfma",
@@ -72,6 +73,8 @@ def load_library():
     lib.tiled_sdpa_bwd.restype = ci
     lib.tiled_sdpa_fwd_gqa.restype = ci
     lib.tiled_sdpa_fwd_gqa.argtypes = [vp] * 5 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
+    lib.tiled_sdpa_fwd_kvcache.restype = ci
+    lib.tiled_sdpa_fwd_kvcache.argtypes = [vp] * 6 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
@@ -178,8 +181,15 @@ def tiled_sdpa_fwd_gqa(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, Hkv, Sq, Skv, 
                                                  splits, workspace_ptr, workspace_bytes))
 
 
+def tiled_sdpa_fwd_kvcache(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, H, Hkv, Sq, Skv, D, scale, dtype,
+                           stream, tile_m=0, tile_n=0, flags=0, splits=0, workspace_ptr=None, workspace_bytes=0) -> int:
+    return int(load_library().tiled_sdpa_fwd_kvcache(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, H, Hkv, Sq,
+                                                     Skv, D, float(scale), dtype, stream, tile_m, tile_n, flags,
+                                                     splits, workspace_ptr, workspace_bytes))
+
+
 def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, return_lse: bool = False,
-            out=None, workspace=None, tile=None, flags: int = 0):
+            out=None, workspace=None, tile=None, flags: int = 0, kv_lens=None):
     """Attention of q [B, H, Sq, D] over k, v [B, H, Skv, D] (KV-cache / decoding shapes), the key range
     split over ``splits`` workgroups per query tile (0 = heuristic).  Under ``causal`` the queries are
     the last Sq positions of the sequence.  ``workspace`` (any contiguous device tensor of enough bytes)
@@ -187,6 +197,9 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
 
     Grouped heads: k, v may be [B, Hkv, Skv, D] with H = G * Hkv, query head h reading key/value head
     h // G (tiled_sdpa_fwd_gqa): the rows of a group share one pass over its keys.
+
+    ``kv_lens`` (int32 device tensor [B]): k, v are a cache of capacity Skv of which batch entry b holds
+    kv_lens[b] valid rows (tiled_sdpa_fwd_kvcache); rows no key reaches come back as zeros.
     """
     import torch
 
@@ -205,6 +218,10 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
         raise ValueError("the number of query heads must be a multiple of the number of key/value heads")
     if k.device != q.device or v.device != q.device:
         raise ValueError("q, k, v must be on one device")
+    if kv_lens is not None:
+        if (not isinstance(kv_lens, torch.Tensor) or kv_lens.dtype != torch.int32 or kv_lens.device != q.device
+                or kv_lens.shape != (q.shape[0],) or not kv_lens.is_contiguous()):
+            raise ValueError("kv_lens must be a contiguous int32 tensor [B] on the device of q")
     B, H, Sq, D = q.shape
     Hkv, Skv = k.shape[1], k.shape[2]
     group = H // Hkv
@@ -226,10 +243,11 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     guard, stream = _guard_and_stream(torch, q.device)
     with guard:
-        st = tiled_sdpa_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
-                                lse.data_ptr() if lse is not None else None,
-                                B, H, Hkv, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
-                                tm, tn, flags, n, ws_ptr, ws_bytes)
+        st = tiled_sdpa_fwd_kvcache(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(),
+                                    lse.data_ptr() if lse is not None else None,
+                                    kv_lens.data_ptr() if kv_lens is not None else None,
+                                    B, H, Hkv, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
+                                    tm, tn, flags, n, ws_ptr, ws_bytes)
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return (out, lse) if return_lse else out

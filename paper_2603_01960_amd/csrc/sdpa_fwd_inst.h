@@ -40,7 +40,7 @@ int launch_one(const LaunchArgs &a)
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
                        a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal,
-                       a.Skv, a.splits, a.ws, a.rows_per_head);
+                       a.Skv, a.splits, a.ws, a.rows_per_head, a.kv_lens, a.heads_per_batch);
     return (int)hipGetLastError();
 }
 

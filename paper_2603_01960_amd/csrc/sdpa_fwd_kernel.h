@@ -130,13 +130,16 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
 // Grouped heads (G query heads reading one key/value head) arrive folded: a "head" of the KV = true
 // kernel is one key/value head and its S = G * Sp rows are the Sp positions of each of the G query
 // heads in turn, so only the causal limit has to know Sp (`rows_per_head`; equal to S when nothing is
-// folded).
+// folded).  With `kv_lens` every batch entry has its own number of valid key rows (a KV cache of
+// capacity Skv_arg rows per head, filled to kv_lens[b]): everything below uses that length, only the
+// distance between heads in memory stays the capacity.
 template <typename T, int D, int NW, int TN, int WPS, bool KV>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
                 float tau, uint32_t qsign, int linear_grid, int causal,
-                int Skv_arg, int splits_arg, float *__restrict__ ws, int rows_per_head)
+                int Skv_arg, int splits_arg, float *__restrict__ ws, int rows_per_head,
+                const int *__restrict__ kv_lens, int heads_per_batch)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     using E = Elem<T>;
@@ -157,11 +160,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int g = lane >> 5, l32 = lane & 31;
 
-    const int Skv = KV ? Skv_arg : S;             // key rows; S is the number of query rows
     const int splits = KV ? splits_arg : 1;
     const int Sp = KV ? rows_per_head : S;        // query positions per query head (S = G * Sp rows when folded)
     const bool folded = KV && Sp != S;
-    const int koff = Skv - Sp;                    // position of a head's query row 0 in the key sequence (causal)
     const int wg = remap_workgroup(blockIdx.x, N, linear_grid != 0);
     // query tile fastest, then split, then head: neighbours share one run of K/V tiles
     const int hs = wg / nQ;
@@ -170,7 +171,14 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // under the causal mask the work of a query tile grows with its index: start the long ones first
     const int qt = causal ? nQ - 1 - (wg - hs * nQ) : wg - hs * nQ;
     const size_t head_off = (size_t)head * (size_t)S * D;
-    const size_t kv_off = (size_t)head * (size_t)Skv * D;
+    const size_t kv_off = (size_t)head * (size_t)(KV ? Skv_arg : S) * D;
+    // key rows of this head; S is the number of query rows
+    int Skv = KV ? Skv_arg : S;
+    if (KV && kv_lens != nullptr) {
+        const int len = kv_lens[head / heads_per_batch];
+        Skv = len < 0 ? 0 : (len < Skv_arg ? len : Skv_arg);
+    }
+    const int koff = Skv - Sp;                    // position of a head's query row 0 in the key sequence (causal)
     const T *qh = q + head_off;
 
     // ---- Q rows of this wavefront as MFMA B-operands: lane holds Q[row l32][kk*16 + g*8 .. +7]
@@ -199,7 +207,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         else          { pos_lo = 0; pos_hi = Sp - 1; }        // the tile crosses into the next query head
         pos_own = qrow_c % Sp;
     }
-    const int nTw = causal ? (pos_hi + koff) / TN + 1 : nT;
+    // (a cache entry shorter than the query block leaves the first rows without any key: reach < 0)
+    const int reach = pos_hi + koff;
+    const int nTw = causal ? (reach < 0 ? 0 : reach / TN + 1) : nT;
     const int klim = causal ? pos_own + koff : Skv - 1;
     const int nfull = ((causal ? pos_lo + koff : Skv - 1) + 1) / TN;
     // this workgroup's run of tiles [t0, t1): all nTw of them unless the key range is split
@@ -460,9 +470,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         }
         return;
     }
-    const float inv = 1.0f / l_tot;
+    // a row that no key reaches (empty cache entry, causal limit before the first key) has l = 0: O = 0, LSE = -inf
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (lse != nullptr && g == 0 && qrow < S)
-        lse[(size_t)head * S + qrow] = (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+        lse[(size_t)head * S + qrow] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f : -INFINITY;
     // (the launcher sizes the dynamic LDS for the larger of the tile slots and this staging area)
     {
         constexpr int CMASK = CPR - 1;                // chunks per row is 8 or 16

@@ -19,6 +19,8 @@ struct LaunchArgs {
     int Skv;          // key/value rows per head (kv = 1)
     int splits;       // workgroups per (head, query tile) along the key axis (kv = 1); > 1 writes partials to ws
     float *ws;        // split workspace: float [BH][splits][S][D] then [BH][splits][S][2]
+    const int *kv_lens;   // kv = 1: NULL, or valid key rows per batch entry (device, int32 [B]); Skv is then the capacity
+    int heads_per_batch;  // kv = 1: key/value heads per batch entry (head / heads_per_batch indexes kv_lens)
     int rows_per_head; // kv = 1: query positions per query head; S / rows_per_head query heads are folded into the S rows
     hipStream_t stream;
 };

@@ -40,17 +40,20 @@ sdpa_merge_kernel(const float *__restrict__ ws, T *__restrict__ o, float *__rest
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
     for (int s = 0; s < splits; ++s) {
         const size_t p = first + (size_t)s * S;
-        const float w = __builtin_amdgcn_exp2f(ml[p * 2] - M);   // 0 for a split with m = -inf (M is finite)
+        // 0 for a split with m = -inf; M itself is -inf only for a row that no key reaches (an empty
+        // cache entry, or a causal limit before the first key): all weights 0, O = 0, LSE = -inf
+        const float w = M == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ml[p * 2] - M);
         L += w * ml[p * 2 + 1];
         const f32x4 part = *(const f32x4 *)(ws + p * D + d4 * 4);
         acc += w * part;
     }
-    const float inv = 1.0f / L;
+    const float inv = L > 0.f ? 1.0f / L : 0.f;
     vec4 out;
 #pragma unroll
     for (int e = 0; e < 4; ++e) out[e] = (T)(acc[e] * inv);
     *(vec4 *)(o + r * D + d4 * 4) = out;
-    if (lse != nullptr && d4 == 0) lse[r] = (M + __builtin_amdgcn_logf(L)) * 0.69314718055994530942f;
+    if (lse != nullptr && d4 == 0)
+        lse[r] = L > 0.f ? (M + __builtin_amdgcn_logf(L)) * 0.69314718055994530942f : -INFINITY;
 #endif
 }
 

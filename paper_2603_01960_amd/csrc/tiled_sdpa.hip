@@ -210,6 +210,15 @@ int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, flo
                        int tile_m, int tile_n, unsigned flags,
                        int splits, void *workspace, unsigned long long workspace_bytes)
 {
+    return tiled_sdpa_fwd_kvcache(q, k, v, o, lse, nullptr, B, H, Hkv, Sq, Skv, D, scale, dtype, stream, tile_m,
+                                  tile_n, flags, splits, workspace, workspace_bytes);
+}
+
+int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o, float *lse, const int *kv_lens,
+                           int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                           int tile_m, int tile_n, unsigned flags,
+                           int splits, void *workspace, unsigned long long workspace_bytes)
+{
     int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
     if (st != TSDPA_OK) return st;
     if (Hkv < 0 || (H > 0 && (Hkv == 0 || H % Hkv != 0))) return TSDPA_ERR_BAD_SHAPE;
@@ -221,7 +230,7 @@ int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, flo
     const int rows = G * Sq;
     if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o;
-    if ((bits & 15u) != 0 || ((uintptr_t)lse & 3u) != 0) return TSDPA_ERR_MISALIGNED;
+    if ((bits & 15u) != 0 || (((uintptr_t)lse | (uintptr_t)kv_lens) & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     if (tile_m == 0 && tile_n == 0)
         pick_tile_kv(rows, Skv, D, &tile_m, &tile_n);
     else if (!(tile_m == 64 || tile_m == 128) || !(tile_n == 32 || tile_n == 64))
@@ -245,6 +254,8 @@ int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, flo
     a.BH = B * Hkv;
     a.S = rows;
     a.rows_per_head = Sq;
+    a.kv_lens = kv_lens;
+    a.heads_per_batch = Hkv;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;

@@ -155,6 +155,16 @@ def test_gqa_entry_point_validation(lib, kwargs, expect):
     assert st == expect, binding.status_string(st)
 
 
+def test_kvcache_entry_point_checks_the_length_array(lib):
+    call = lambda lens, **kw: binding.tiled_sdpa_fwd_kvcache(P, P, P, P, None, lens, kw.get("B", 2), 8, 2, 1, 700, 64,
+                                                             0.125, 1, None, 0, 0, 0, 1, None, 0)
+    assert binding.tiled_sdpa_fwd_kvcache(None, P, P, P, None, P, 2, 8, 2, 1, 700, 64, 0.125, 1, None) == NULL
+    assert binding.tiled_sdpa_fwd_kvcache(P, P, P, P, None, P + 2, 2, 8, 2, 1, 700, 64, 0.125, 1, None,
+                                          0, 0, 0, 1, None, 0) == ALIGN
+    assert call(P + 2, B=0) == OK                   # empty problem: nothing else is looked at
+    assert binding.tiled_sdpa_fwd_kvcache(P, P, P, P, None, P, 2, 8, 3, 1, 700, 64, 0.125, 1, None) == SHAPE
+
+
 def test_kv_workspace_size_and_default_splits(lib):
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 1) == 0
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 0) == 0

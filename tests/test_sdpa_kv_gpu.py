@@ -261,3 +261,67 @@ def test_head_counts_that_do_not_divide_are_refused():
     st = binding.tiled_sdpa_fwd_gqa(q.data_ptr(), k.data_ptr(), v.data_ptr(), q.data_ptr(), None,
                                     1, 7, 2, 4, 64, 64, 0.125, binding.F16, None)
     assert st == 2
+
+
+# ------------------------------------------------------------------ KV cache with a length per batch entry
+def check_kv_lens(B, H, Hkv, Sq, cap, D, dtype, lens, causal, splits, tile=None):
+    """Entry b against the oracle on its first lens[b] key rows (the plain definition on the valid part of
+    the cache).  Rows past the length are NaN in the device tensors: nothing of them may reach the output.
+    A row that no key reaches must come back as exactly 0 with LSE = -inf."""
+    G = H // Hkv
+    q = make_qkv(B, H, Sq, D, dtype, seed=81)[0]
+    _, k, v = make_qkv(B, Hkv, cap, D, dtype, seed=82)
+    kd, vd = k.clone(), v.clone()
+    for b, n in enumerate(lens):
+        kd[b, :, n:] = float("nan")
+        vd[b, :, n:] = float("nan")
+    say(f"[case] kv_lens B={B} H={H} Hkv={Hkv} Sq={Sq} cap={cap} D={D} {dtype} lens={lens} causal={causal} splits={splits} tile={tile}")
+    lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    o, lse = binding.sdpa_kv(q.cuda(), kd.cuda(), vd.cuda(), causal=causal, splits=splits, tile=tile,
+                             return_lse=True, kv_lens=lens_d)
+    torch.cuda.synchronize()
+    o, lse = o.cpu(), lse.cpu()
+    worst = 0.0
+    for b, n in enumerate(lens):
+        first = max(0, Sq - n) if causal else (Sq if n == 0 else 0)       # rows before `first` see no key
+        assert torch.all(o[b, :, :first] == 0), f"entry {b}: rows without keys must be zero"
+        assert torch.all(lse[b, :, :first] == float("-inf")), f"entry {b}: LSE of rows without keys must be -inf"
+        if first == Sq:
+            continue
+        kx = np.repeat(k[b:b + 1, :, :n].float().numpy(), G, axis=1)
+        vx = np.repeat(v[b:b + 1, :, :n].float().numpy(), G, axis=1)
+        ref_o, ref_lse = orc.sdpa(q[b:b + 1, :, first:].float().numpy(), kx, vx, return_lse=True, causal=causal)
+        got_o, got_lse = o[b:b + 1, :, first:].double().numpy(), lse[b:b + 1, :, first:].double().numpy()
+        assert np.isfinite(got_o).all() and np.isfinite(got_lse).all(), f"entry {b}: non-finite output"
+        err, lerr = float(np.abs(got_o - ref_o).max()), float(np.abs(got_lse - ref_lse).max())
+        worst = max(worst, err)
+        assert err <= TOL[dtype], f"entry {b} (len {n}): max|dO| {err}"
+        assert lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16), f"entry {b} (len {n}): max|dLSE| {lerr}"
+    say(f"        worst max|dO|={worst:.3e}")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("splits", [0, 1, 4])
+def test_decoding_step_over_a_cache_with_a_length_per_entry(dtype, causal, splits):
+    check_kv_lens(5, 8, 2, 1, 700, 128, dtype, [700, 1, 333, 0, 64], causal, splits)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("tile", [None, (64, 32), (128, 64)])
+def test_prefill_chunks_over_a_cache_with_a_length_per_entry(dtype, tile):
+    # entry 2 holds fewer positions than the chunk has rows: its first 28 rows precede every key
+    check_kv_lens(3, 4, 4, 48, 300, 64, dtype, [300, 48, 20], True, 0, tile)
+    check_kv_lens(3, 6, 2, 48, 300, 64, dtype, [257, 300, 5], True, 3, tile)
+    check_kv_lens(2, 4, 1, 5, 1000, 96, dtype, [999, 31], False, 0, tile)
+
+
+def test_lengths_beyond_the_capacity_are_clamped():
+    check_kv_lens(2, 2, 2, 1, 100, 64, "f16", [100, 100], False, 0)
+    q = make_qkv(2, 2, 1, 64, "f16", seed=83)[0].cuda()
+    _, k, v = (t.cuda() for t in make_qkv(2, 2, 100, 64, "f16", seed=84))
+    a = binding.sdpa_kv(q, k, v, kv_lens=torch.tensor([100, 100], dtype=torch.int32, device="cuda"))
+    b = binding.sdpa_kv(q, k, v, kv_lens=torch.tensor([5000, -3], dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert torch.equal(a[0], b[0])                  # 5000 > capacity: the whole cache
+    assert torch.all(b[1] == 0)                     # negative: an empty entry
