@@ -116,3 +116,41 @@ def test_backward_replays_bit_exactly():
         torch.cuda.synchronize()
         for name, got, want in zip(("dq", "dk", "dv"), grads, ref):
             assert torch.equal(got, want), f"replay {rep}: {name} differs from the eager launch"
+
+
+def test_host_threads_on_their_own_streams_do_not_disturb_each_other():
+    """The library keeps no state besides its kernel table (set up under std::call_once): four host
+    threads launch different problems on their own streams at the same time, each repeatedly, and every
+    result must equal the one computed alone."""
+    import threading
+
+    say("[case] four host threads, four streams")
+    problems = []
+    for i, (S, D, dtype, causal) in enumerate([(700, 128, "bf16", False), (333, 64, "f16", True),
+                                               (1024, 96, "bf16", True), (150, 160, "f16", False)]):
+        q, k, v = (t.cuda() for t in make_qkv(2, 4, S, D, dtype, seed=500 + i))
+        ref = binding.sdpa(q, k, v, causal=causal, return_lse=True)
+        problems.append((q, k, v, causal, ref))
+    torch.cuda.synchronize()
+    failures = []
+
+    def work(idx):
+        q, k, v, causal, (o_ref, lse_ref) = problems[idx]
+        stream = torch.cuda.Stream()
+        try:
+            with torch.cuda.stream(stream):
+                for rep in range(20):
+                    o, lse = binding.sdpa(q, k, v, causal=causal, return_lse=True)
+                    stream.synchronize()
+                    if not (torch.equal(o, o_ref) and torch.equal(lse, lse_ref)):
+                        failures.append((idx, rep))
+        except Exception as e:          # surfaced below: an exception in a thread would otherwise be lost
+            failures.append((idx, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a worker did not finish"
+    assert not failures, failures
