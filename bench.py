@@ -55,6 +55,9 @@ def parse_args():
     ap.add_argument("--kv-fill", type=float, default=0.0,
                     help="with --kv: treat Skv as the capacity of a cache filled to this fraction in every batch entry "
                          "(tiled_sdpa_fwd_kvcache with a length per entry); 0 = a full cache without lengths")
+    ap.add_argument("--kv-block", type=int, default=0,
+                    help="with --kv: store the cache in pages of this many rows, scattered over the pool in a seeded "
+                         "random order (tiled_sdpa_fwd_paged); Skv must be a multiple of it")
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="with --kv: key/value heads (grouped heads: H query heads share H/kv-heads of them; 0 = H)")
     ap.add_argument("--bwd", action="store_true",
@@ -256,6 +259,22 @@ def bench_kv(pkg, torch, args, tile, flags):
         Skv = max(1, int(round(cap * min(1.0, args.kv_fill))))          # valid rows per entry: what is read and computed
         lens = torch.full((B,), Skv, dtype=torch.int32, device="cuda")
     run = lambda: pkg.sdpa_kv(q, k, v, splits=splits, out=o, workspace=ws, tile=tile, flags=flags, kv_lens=lens)
+    if args.kv_block:
+        R = args.kv_block
+        nb = cap // R
+        assert nb * R == cap, "--kv-block must divide Skv"
+        if lens is None:
+            lens = torch.full((B,), cap, dtype=torch.int32, device="cuda")
+        perm = torch.randperm(B * nb, generator=torch.Generator().manual_seed(4244)).to(torch.int32)
+        table = perm.view(B, nb).contiguous().cuda()
+        def paged(t):       # [B, Hkv, cap, D] -> pages [B*nb, Hkv, R, D], block (b, i) stored at page table[b][i]
+            blocks = t.view(B, Hkv, nb, R, D).permute(0, 2, 1, 3, 4).reshape(B * nb, Hkv, R, D)
+            out = torch.empty(blocks.shape, dtype=blocks.dtype, device=blocks.device)
+            out[perm.long().cuda()] = blocks
+            return out
+        kp, vp = paged(k), paged(v)
+        del k, v
+        run = lambda: pkg.sdpa_paged(q, kp, vp, lens, table, splits=splits, out=o, workspace=ws, tile=tile, flags=flags)
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
@@ -290,7 +309,7 @@ def bench_kv(pkg, torch, args, tile, flags):
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
         "config": {"workload": f"KV: SDPA fwd {'causal' if causal else 'non-causal'} B={B} H={H}{'' if G == 1 else f' (kv heads {Hkv})'} Sq={Sq} Skv={Skv} D={D} {dtype}",
-                   "cache_capacity": cap, "splits": splits, "tile": list(tile) if tile else "heuristic",
+                   "cache_capacity": cap, "page_rows": args.kv_block or None, "splits": splits, "tile": list(tile) if tile else "heuristic",
                    "cache_tokens_per_s": round(B * Hkv * Skv / (ms * 1e-3), 1)},
         "roofline": roofline}), flush=True)
 

@@ -175,6 +175,37 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
                            int tile_m, int tile_n, unsigned flags,
                            int splits, void *workspace, unsigned long long workspace_bytes);
 
+/*
+ * tiled_sdpa_fwd_kvcache over a PAGED cache (the KV-cache variants of the paper's roadmap, Section 8,
+ * in the form serving systems store them): keys and values live in pages of block_rows rows that any
+ * batch entry may own in any order.
+ *
+ *   k_pages, v_pages : [P, Hkv, block_rows, D], P pages (P is not passed: the table names the pages);
+ *                      16-byte aligned.  block_rows is 64, 128, 256, ... (a power of two >= 64, so that a
+ *                      K/V tile of 32 or 64 rows lies within one page).
+ *   block_table      : device, int32 [B, max_blocks], 4-byte aligned: block_table[b][i] is the page
+ *                      holding key rows i*block_rows ... (i+1)*block_rows - 1 of batch entry b.  Only
+ *                      the entries below ceil(kv_lens[b] / block_rows) are used; the others may hold
+ *                      anything.  The pages named must exist; the library cannot check that.
+ *   kv_lens          : device, int32 [B]: valid key rows of entry b, clamped to
+ *                      [0, max_blocks * block_rows].  Required (not NULL).
+ *   q, o, lse, H, Hkv, Sq, D, scale, dtype, stream, tiles, flags, splits, workspace: as for
+ *                      tiled_sdpa_fwd_kvcache with capacity Skv = max_blocks * block_rows (that is
+ *                      what shapes are validated against and what the split heuristic sees).
+ *
+ * Both arrays are read by the kernels when they run.  Every K/V tile is fetched through a buffer
+ * descriptor of its own that starts at the tile's rows within its page and is as long as the tile has
+ * valid rows, so neither rows past kv_lens[b] nor pages past the last one are touched.  Results are
+ * those of tiled_sdpa_fwd_kvcache on the same rows gathered into a dense cache.  block_rows not a
+ * power of two >= 64, max_blocks < 0 or max_blocks * block_rows overflowing an int is
+ * TSDPA_ERR_BAD_SHAPE; kv_lens or block_table NULL with B*H*Sq > 0 is TSDPA_ERR_NULL_PTR.
+ */
+int tiled_sdpa_fwd_paged(const void *q, const void *k_pages, const void *v_pages, void *o, float *lse,
+                         const int *kv_lens, const int *block_table,
+                         int B, int H, int Hkv, int Sq, int max_blocks, int block_rows, int D,
+                         float scale, int dtype, void *stream, int tile_m, int tile_n, unsigned flags,
+                         int splits, void *workspace, unsigned long long workspace_bytes);
+
 /* Splits the heuristic picks (1 when the query tiles alone fill the GPU); returns a status code. */
 int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype, unsigned flags, int *splits);
 

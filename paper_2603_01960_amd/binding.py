@@ -28,6 +28,7 @@ EXPORTS = (
     "tiled_sdpa_fwd_kv",
     "tiled_sdpa_fwd_gqa",
     "tiled_sdpa_fwd_kvcache",
+    "tiled_sdpa_fwd_paged",
     "tiled_sdpa_kv_default_splits",
     "tiled_sdpa_kv_workspace_bytes",
     "tiled_sdpa_probe_mfma",
@@ -75,6 +76,8 @@ def load_library():
     lib.tiled_sdpa_fwd_gqa.argtypes = [vp] * 5 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_fwd_kvcache.restype = ci
     lib.tiled_sdpa_fwd_kvcache.argtypes = [vp] * 6 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
+    lib.tiled_sdpa_fwd_paged.restype = ci
+    lib.tiled_sdpa_fwd_paged.argtypes = [vp] * 7 + [ci] * 7 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
@@ -248,6 +251,67 @@ def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, retur
                                     kv_lens.data_ptr() if kv_lens is not None else None,
                                     B, H, Hkv, Sq, Skv, D, math.nan if scale is None else scale, dtype, stream,
                                     tm, tn, flags, n, ws_ptr, ws_bytes)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return (out, lse) if return_lse else out
+
+
+def tiled_sdpa_fwd_paged(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, block_table_ptr, B, H, Hkv, Sq, max_blocks,
+                         block_rows, D, scale, dtype, stream, tile_m=0, tile_n=0, flags=0, splits=0,
+                         workspace_ptr=None, workspace_bytes=0) -> int:
+    return int(load_library().tiled_sdpa_fwd_paged(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, block_table_ptr,
+                                                   B, H, Hkv, Sq, max_blocks, block_rows, D, float(scale), dtype,
+                                                   stream, tile_m, tile_n, flags, splits, workspace_ptr, workspace_bytes))
+
+
+def sdpa_paged(q, k_pages, v_pages, kv_lens, block_table, causal: bool = False, scale=None, *, splits: int = 0,
+               return_lse: bool = False, out=None, workspace=None, tile=None, flags: int = 0):
+    """Attention of q [B, H, Sq, D] over a paged cache: k_pages, v_pages [P, Hkv, block_rows, D],
+    block_table int32 [B, max_blocks] (page of every block of every batch entry), kv_lens int32 [B]
+    (valid key rows per entry).  See tiled_sdpa_fwd_paged; otherwise as :func:`sdpa_kv`."""
+    import torch
+
+    if causal:
+        flags |= FLAG_CAUSAL
+    for name, t in (("q", q), ("k_pages", k_pages), ("v_pages", v_pages)):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dim() != 4 or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous 4-d device tensor")
+    if q.dtype not in (torch.float16, torch.bfloat16) or k_pages.dtype != q.dtype or v_pages.dtype != q.dtype:
+        raise ValueError("q, k_pages, v_pages must share dtype float16 or bfloat16")
+    if k_pages.shape != v_pages.shape or k_pages.shape[3] != q.shape[3] or k_pages.device != q.device or v_pages.device != q.device:
+        raise ValueError("k_pages, v_pages must be [P, Hkv, block_rows, D] on the device of q")
+    B, H, Sq, D = q.shape
+    P, Hkv, block_rows = k_pages.shape[:3]
+    if Hkv == 0 or H % Hkv != 0:
+        raise ValueError("the number of query heads must be a multiple of the number of key/value heads")
+    for name, t, shape in (("kv_lens", kv_lens, (B,)), ("block_table", block_table, None)):
+        if (not isinstance(t, torch.Tensor) or t.dtype != torch.int32 or t.device != q.device or not t.is_contiguous()
+                or (shape is not None and tuple(t.shape) != shape)):
+            raise ValueError(f"{name} must be a contiguous int32 device tensor" + (f" {list(shape)}" if shape else ""))
+    if block_table.dim() != 2 or block_table.shape[0] != B:
+        raise ValueError("block_table must be [B, max_blocks]")
+    max_blocks = block_table.shape[1]
+    dtype = F16 if q.dtype == torch.float16 else BF16
+    if out is None:
+        out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != q.dtype or not out.is_contiguous() or out.device != q.device:
+        raise ValueError("out must match q in shape, dtype, device and be contiguous")
+    lse = torch.empty((B, H, Sq), dtype=torch.float32, device=q.device) if return_lse else None
+    tm, tn = tile if tile is not None else (0, 0)
+    group = H // Hkv
+    n = splits if splits else kv_default_splits(B, Hkv, group * Sq, max(1, max_blocks * block_rows), D, dtype,
+                                                flags & ~FLAG_CAUSAL)
+    need = kv_workspace_bytes(B, H, Sq, D, n)
+    if workspace is None and need:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    guard, stream = _guard_and_stream(torch, q.device)
+    with guard:
+        st = tiled_sdpa_fwd_paged(q.data_ptr(), k_pages.data_ptr(), v_pages.data_ptr(), out.data_ptr(),
+                                  lse.data_ptr() if lse is not None else None, kv_lens.data_ptr(),
+                                  block_table.data_ptr(), B, H, Hkv, Sq, max_blocks, block_rows, D,
+                                  math.nan if scale is None else scale, dtype, stream, tm, tn, flags, n, ws_ptr, ws_bytes)
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return (out, lse) if return_lse else out

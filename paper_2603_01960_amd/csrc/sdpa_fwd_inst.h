@@ -20,7 +20,7 @@ constexpr int kLdsPerCU = 160 * 1024;
 // halves and move them back and forth (or to scratch) inside the loop.
 template <int D, int NW, int TN> constexpr int waves_per_simd() { return (TN == 32 && D <= 128) ? 3 : 2; }
 
-template <typename T, int D, int NW, int TN, bool KV = false>
+template <typename T, int D, int NW, int TN, int KV = 0>     // 0 square, 1 dense cache, 2 paged cache
 int launch_one(const LaunchArgs &a)
 {
     constexpr int WPS = waves_per_simd<D, NW, TN>();
@@ -40,7 +40,8 @@ int launch_one(const LaunchArgs &a)
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
                        a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal,
-                       a.Skv, a.splits, a.ws, a.rows_per_head, a.kv_lens, a.heads_per_batch);
+                       a.Skv, a.splits, a.ws, a.rows_per_head, a.kv_lens, a.heads_per_batch,
+                       a.block_table, a.max_blocks, a.block_shift);
     return (int)hipGetLastError();
 }
 
@@ -48,12 +49,21 @@ template <typename T, int D>
 int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a)
 {
     const int key = tile_m * 1000 + tile_n;
+    if (a.kv && a.block_table != nullptr) {
+        switch (key) {
+            case 64032: return launch_one<T, D, 2, 32, 2>(a);
+            case 64064: return launch_one<T, D, 2, 64, 2>(a);
+            case 128032: return launch_one<T, D, 4, 32, 2>(a);
+            case 128064: return launch_one<T, D, 4, 64, 2>(a);
+            default: return (int)hipErrorInvalidValue;
+        }
+    }
     if (a.kv) {
         switch (key) {
-            case 64032: return launch_one<T, D, 2, 32, true>(a);
-            case 64064: return launch_one<T, D, 2, 64, true>(a);
-            case 128032: return launch_one<T, D, 4, 32, true>(a);
-            case 128064: return launch_one<T, D, 4, 64, true>(a);
+            case 64032: return launch_one<T, D, 2, 32, 1>(a);
+            case 64064: return launch_one<T, D, 2, 64, 1>(a);
+            case 128032: return launch_one<T, D, 4, 32, 1>(a);
+            case 128064: return launch_one<T, D, 4, 64, 1>(a);
             default: return (int)hipErrorInvalidValue;
         }
     }

@@ -132,16 +132,24 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
 // heads in turn, so only the causal limit has to know Sp (`rows_per_head`; equal to S when nothing is
 // folded).  With `kv_lens` every batch entry has its own number of valid key rows (a KV cache of
 // capacity Skv_arg rows per head, filled to kv_lens[b]): everything below uses that length, only the
-// distance between heads in memory stays the capacity.
-template <typename T, int D, int NW, int TN, int WPS, bool KV>
+// distance between heads in memory stays the capacity.  With `block_table` the cache is paged: K and V
+// are [pages][heads_per_batch][block_rows][D], block_table[b][i] names the page that holds key rows
+// i * block_rows ... of batch entry b, and every K/V tile (block_rows is a multiple of the tile) gets a
+// buffer descriptor of its own, based at its page and as long as the tile has valid rows.
+// KVM: 0 = the paper's square problem, 1 = the general kernel over a dense cache, 2 = over a paged cache
+// (an instantiation of its own: the per-tile descriptors cost scalar registers in the loop, which the
+// latency-bound small decoding shapes of the dense path would pay for too).
+template <typename T, int D, int NW, int TN, int WPS, int KVM>
 __global__ void __launch_bounds__(NW * 64, WPS)  // WPS = wavefronts per SIMD the register budget is sized for
 sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 T *__restrict__ o, float *__restrict__ lse, int S, int nQ, int N, float c,
                 float tau, uint32_t qsign, int linear_grid, int causal,
                 int Skv_arg, int splits_arg, float *__restrict__ ws, int rows_per_head,
-                const int *__restrict__ kv_lens, int heads_per_batch)
+                const int *__restrict__ kv_lens, int heads_per_batch,
+                const int *__restrict__ block_table, int max_blocks, int block_shift)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
+    constexpr bool KV = KVM != 0, PAGED = KVM == 2;
     using E = Elem<T>;
     using vec8 = typename E::vec8;
     using vec4 = typename E::vec4;
@@ -179,6 +187,14 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         Skv = len < 0 ? 0 : (len < Skv_arg ? len : Skv_arg);
     }
     const int koff = Skv - Sp;                    // position of a head's query row 0 in the key sequence (causal)
+    // paged cache: this batch entry's row of the block table, and the head's index within a page
+    const int *pages = nullptr;
+    int page_head = 0;
+    if constexpr (PAGED) {
+        const int b = head / heads_per_batch;
+        page_head = head - b * heads_per_batch;
+        pages = block_table + (size_t)b * max_blocks;
+    }
     const T *qh = q + head_off;
 
     // ---- Q rows of this wavefront as MFMA B-operands: lane holds Q[row l32][kk*16 + g*8 .. +7]
@@ -233,12 +249,25 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
         v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
     }
-    auto load_tile = [&](decltype(k_rsrc) rsrc, const int (&goff)[NLD], int j, lds_ptr dst) __attribute__((always_inline)) {
+    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NLD], int j, lds_ptr dst) __attribute__((always_inline)) {
+        auto rsrc = whole;
         // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
         // outside the descriptor and read as zeros without a memory access, and so does a tile this
         // workgroup does not need (its index is moved past the end)
-        const int soff = (j < t1 ? j : nT) * G::GTILE;
+        int soff = (j < t1 ? j : nT) * G::GTILE;
+        if constexpr (PAGED) {
+            // the tile lies within one page: a descriptor from the page's rows of this head, covering
+            // the tile's valid rows only (none for a tile this workgroup does not need)
+            const int row0 = j * TN;
+            int valid = j < t1 ? Skv - row0 : 0;
+            valid = valid < 0 ? 0 : (valid < TN ? valid : TN);
+            const int blk = row0 >> block_shift;
+            const int page = pages[blk < max_blocks ? blk : 0];
+            const size_t first = (((size_t)page * heads_per_batch + page_head) << block_shift) + (row0 - (blk << block_shift));
+            rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(tensor + first * D), (short)0, valid * G::GROW, 0x00020000);
+            soff = 0;
+        }
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
@@ -399,8 +428,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
     // ahead cost 32 registers and measured 4 % slower).
     if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
-    load_tile(k_rsrc, k_goff, t0, lds + KSLOT0);
-    load_tile(v_rsrc, v_goff, t0, lds + VSLOT0);
+    load_tile(k, k_rsrc, k_goff, t0, lds + KSLOT0);
+    load_tile(v, v_rsrc, v_goff, t0, lds + VSLOT0);
     TSDPA_WAIT_VMCNT0();
     __syncthreads();
 
@@ -408,8 +437,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     auto step = [&](int j, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
         if (j + 1 < t1) {
-            load_tile(k_rsrc, k_goff, j + 1, lds + (PAR ? KSLOT0 : KSLOT1));
-            load_tile(v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
+            load_tile(k, k_rsrc, k_goff, j + 1, lds + (PAR ? KSLOT0 : KSLOT1));
+            load_tile(v, v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
         }
         // the MFMAs of a step form chains fed by LDS reads: a raised wavefront priority lets them go
         // ahead of the other wavefronts' vector work whenever their operands are ready (+1-3 %), and

@@ -21,6 +21,8 @@ struct LaunchArgs {
     float *ws;        // split workspace: float [BH][splits][S][D] then [BH][splits][S][2]
     const int *kv_lens;   // kv = 1: NULL, or valid key rows per batch entry (device, int32 [B]); Skv is then the capacity
     int heads_per_batch;  // kv = 1: key/value heads per batch entry (head / heads_per_batch indexes kv_lens)
+    const int *block_table; // kv = 1: NULL, or pages of a paged cache (device, int32 [B][max_blocks]); k, v are then [pages][heads_per_batch][1 << block_shift][D]
+    int max_blocks, block_shift;
     int rows_per_head; // kv = 1: query positions per query head; S / rows_per_head query heads are folded into the S rows
     hipStream_t stream;
 };

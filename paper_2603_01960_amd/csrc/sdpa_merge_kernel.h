@@ -34,10 +34,14 @@ sdpa_merge_kernel(const float *__restrict__ ws, T *__restrict__ o, float *__rest
     const float *ml = ws + rows * splits * D;
     const size_t first = (bh * splits) * S + row; // split s sits s*S rows further on
 
+    // both loops are chains of independent loads: unrolled so that eight of them are in flight at a time
+    // (with many splits and few rows this kernel is pure load latency)
     float M = -INFINITY;
+#pragma unroll 8
     for (int s = 0; s < splits; ++s) M = fmaxf(M, ml[(first + (size_t)s * S) * 2]);
     float L = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 8
     for (int s = 0; s < splits; ++s) {
         const size_t p = first + (size_t)s * S;
         // 0 for a split with m = -inf; M itself is -inf only for a row that no key reaches (an empty

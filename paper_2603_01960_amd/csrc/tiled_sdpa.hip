@@ -96,6 +96,12 @@ void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 
 }  // namespace
 
+static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, float *lse, const int *kv_lens,
+                       const int *block_table, int max_blocks, int block_shift,
+                       int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                       int tile_m, int tile_n, unsigned flags,
+                       int splits, void *workspace, unsigned long long workspace_bytes);
+
 extern "C" {
 
 int tiled_sdpa_version(void) { return kVersion; }
@@ -219,6 +225,40 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
                            int tile_m, int tile_n, unsigned flags,
                            int splits, void *workspace, unsigned long long workspace_bytes)
 {
+    return fwd_kv_impl(q, k, v, o, lse, kv_lens, nullptr, 0, 0, B, H, Hkv, Sq, Skv, D, scale, dtype, stream, tile_m,
+                       tile_n, flags, splits, workspace, workspace_bytes);
+}
+
+int tiled_sdpa_fwd_paged(const void *q, const void *k_pages, const void *v_pages, void *o, float *lse,
+                         const int *kv_lens, const int *block_table,
+                         int B, int H, int Hkv, int Sq, int max_blocks, int block_rows, int D,
+                         float scale, int dtype, void *stream, int tile_m, int tile_n, unsigned flags,
+                         int splits, void *workspace, unsigned long long workspace_bytes)
+{
+    // pages of 64 << n rows, so that a K/V tile of 32 or 64 rows never straddles two pages
+    int shift = 6;
+    while (shift < 20 && (1 << shift) != block_rows) ++shift;
+    if (max_blocks < 0 || (1 << shift) != block_rows) return TSDPA_ERR_BAD_SHAPE;
+    if ((int64_t)max_blocks * block_rows > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
+    const int cap = max_blocks * block_rows;
+    const int st = validate_shape_kv(B, H, Sq, cap, D, dtype, flags);
+    if (st != TSDPA_OK) return st;
+    if ((int64_t)B * H * Sq != 0 && (!kv_lens || !block_table)) return TSDPA_ERR_NULL_PTR;
+    if (((uintptr_t)block_table & 3u) != 0) return TSDPA_ERR_MISALIGNED;
+    return fwd_kv_impl(q, k_pages, v_pages, o, lse, kv_lens, block_table, max_blocks, shift, B, H, Hkv, Sq, cap, D,
+                       scale, dtype, stream, tile_m, tile_n, flags, splits, workspace, workspace_bytes);
+}
+
+}  // extern "C"
+
+// Everything behind tiled_sdpa_fwd_kv / _gqa / _kvcache / _paged: one query block per query head against a
+// cache of Skv rows per key/value head, dense (block_table NULL) or paged.
+static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, float *lse, const int *kv_lens,
+                       const int *block_table, int max_blocks, int block_shift,
+                       int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
+                       int tile_m, int tile_n, unsigned flags,
+                       int splits, void *workspace, unsigned long long workspace_bytes)
+{
     int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
     if (st != TSDPA_OK) return st;
     if (Hkv < 0 || (H > 0 && (Hkv == 0 || H % Hkv != 0))) return TSDPA_ERR_BAD_SHAPE;
@@ -256,6 +296,9 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
     a.rows_per_head = Sq;
     a.kv_lens = kv_lens;
     a.heads_per_batch = Hkv;
+    a.block_table = block_table;
+    a.max_blocks = max_blocks;
+    a.block_shift = block_shift;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;
@@ -297,6 +340,8 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
     }
     return TSDPA_OK;
 }
+
+extern "C" {
 
 unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S)
 {

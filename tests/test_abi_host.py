@@ -165,6 +165,36 @@ def test_kvcache_entry_point_checks_the_length_array(lib):
     assert binding.tiled_sdpa_fwd_kvcache(P, P, P, P, None, P, 2, 8, 3, 1, 700, 64, 0.125, 1, None) == SHAPE
 
 
+@pytest.mark.parametrize("kwargs,expect", [
+    (dict(), WORKSPACE),                           # everything passes up to the workspace (splits = 2, none given)
+    (dict(block_rows=48), SHAPE),                   # not a power of two
+    (dict(block_rows=32), SHAPE),                   # a 64-row K/V tile would straddle two pages
+    (dict(block_rows=96), SHAPE),
+    (dict(block_rows=0), SHAPE),
+    (dict(max_blocks=-1), SHAPE),
+    (dict(max_blocks=1 << 25, block_rows=1024), SHAPE),     # capacity overflows an int
+    (dict(max_blocks=1 << 14, block_rows=1024), SHAPE),     # capacity beyond the 2^30-byte head range
+    (dict(lens=None), NULL),
+    (dict(table=None), NULL),
+    (dict(table=P + 2), ALIGN),
+    (dict(lens=P + 1), ALIGN),
+    (dict(Hkv=3), SHAPE),
+    (dict(B=0, lens=None, table=None), OK),
+    (dict(D=72), BAD_D),
+    (dict(Sq=5000, flags=binding.FLAG_CAUSAL), SHAPE),      # more query rows than the cache can hold
+    (dict(splits=1), NULL),                        # q = None: reached only after every check above
+])
+def test_paged_entry_point_validation(lib, kwargs, expect):
+    a = dict(q=P, lens=P, table=P, B=2, H=8, Hkv=2, Sq=1, max_blocks=16, block_rows=256, D=128, flags=0, splits=2)
+    a.update(kwargs)
+    if kwargs.get("splits") == 1:
+        a["q"] = None
+    st = binding.tiled_sdpa_fwd_paged(a["q"], P, P, P, None, a["lens"], a["table"], a["B"], a["H"], a["Hkv"], a["Sq"],
+                                      a["max_blocks"], a["block_rows"], a["D"], 0.125, 1, None, 0, 0, a["flags"],
+                                      a["splits"], None, 0)
+    assert st == expect, binding.status_string(st)
+
+
 def test_kv_workspace_size_and_default_splits(lib):
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 1) == 0
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 0) == 0

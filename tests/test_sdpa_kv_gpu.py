@@ -325,3 +325,81 @@ def test_lengths_beyond_the_capacity_are_clamped():
     torch.cuda.synchronize()
     assert torch.equal(a[0], b[0])                  # 5000 > capacity: the whole cache
     assert torch.all(b[1] == 0)                     # negative: an empty entry
+
+
+# ------------------------------------------------------------------ paged cache
+def check_paged(B, H, Hkv, Sq, D, dtype, lens, block_rows, causal, splits, tile=None, seed=91):
+    """Dense per-entry caches are cut into pages that are scattered over a pool in a seeded random order
+    (unused pool pages and the unused tail of every last page hold NaN); the oracle sees the dense rows."""
+    G = H // Hkv
+    cap = max(1, max(lens))
+    max_blocks = (cap + block_rows - 1) // block_rows
+    q = make_qkv(B, H, Sq, D, dtype, seed=seed)[0]
+    _, k, v = make_qkv(B, Hkv, max_blocks * block_rows, D, dtype, seed=seed + 1)
+    used = [(n + block_rows - 1) // block_rows for n in lens]
+    pool = sum(used) + 3                                    # a few pages nobody owns
+    rng = np.random.default_rng(seed)
+    order = rng.permutation(pool)
+    kp = torch.full((pool, Hkv, block_rows, D), float("nan"), dtype=k.dtype)
+    vp = torch.full((pool, Hkv, block_rows, D), float("nan"), dtype=v.dtype)
+    table = np.full((B, max(1, max_blocks)), -12345, dtype=np.int32)    # unused slots: garbage that must not be followed
+    nxt = 0
+    for b in range(B):
+        for i in range(used[b]):
+            page = int(order[nxt]); nxt += 1
+            table[b, i] = page
+            rows = min(block_rows, lens[b] - i * block_rows)
+            kp[page, :, :rows] = k[b, :, i * block_rows:i * block_rows + rows]
+            vp[page, :, :rows] = v[b, :, i * block_rows:i * block_rows + rows]
+    say(f"[case] paged B={B} H={H} Hkv={Hkv} Sq={Sq} D={D} {dtype} lens={lens} block_rows={block_rows} causal={causal} splits={splits} tile={tile}")
+    o, lse = binding.sdpa_paged(q.cuda(), kp.cuda(), vp.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                                torch.from_numpy(table).cuda(), causal=causal, splits=splits, tile=tile, return_lse=True)
+    torch.cuda.synchronize()
+    o, lse = o.cpu(), lse.cpu()
+    for b, n in enumerate(lens):
+        first = max(0, Sq - n) if causal else (Sq if n == 0 else 0)
+        assert torch.all(o[b, :, :first] == 0) and torch.all(lse[b, :, :first] == float("-inf"))
+        if first == Sq:
+            continue
+        kx = np.repeat(k[b:b + 1, :, :n].float().numpy(), G, axis=1)
+        vx = np.repeat(v[b:b + 1, :, :n].float().numpy(), G, axis=1)
+        ref_o, ref_lse = orc.sdpa(q[b:b + 1, :, first:].float().numpy(), kx, vx, return_lse=True, causal=causal)
+        got_o, got_lse = o[b:b + 1, :, first:].double().numpy(), lse[b:b + 1, :, first:].double().numpy()
+        assert np.isfinite(got_o).all() and np.isfinite(got_lse).all(), f"entry {b}: non-finite output"
+        err, lerr = float(np.abs(got_o - ref_o).max()), float(np.abs(got_lse - ref_lse).max())
+        assert err <= TOL[dtype], f"entry {b} (len {n}): max|dO| {err}"
+        assert lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16), f"entry {b} (len {n}): max|dLSE| {lerr}"
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("block_rows", [64, 256])
+@pytest.mark.parametrize("splits", [0, 1, 5])
+def test_decoding_step_over_a_paged_cache(dtype, block_rows, splits):
+    check_paged(5, 8, 2, 1, 128, dtype, [700, 1, 333, 0, 64], block_rows, True, splits)
+    check_paged(3, 4, 4, 1, 64, dtype, [block_rows, 2 * block_rows + 1, 3 * block_rows - 1], block_rows, False, splits)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("tile", [None, (64, 32), (64, 64), (128, 32), (128, 64)])
+def test_prefill_chunks_over_a_paged_cache(dtype, tile):
+    check_paged(3, 6, 2, 48, 64, dtype, [300, 48, 20], 64, True, 0, tile)
+    check_paged(2, 4, 1, 130, 128, dtype, [1000, 131], 128, True, 3, tile)
+    check_paged(2, 2, 2, 5, 96, dtype, [515, 31], 512, False, 0, tile)
+    check_paged(1, 2, 1, 3, 160, dtype, [200], 64, True, 2, tile)
+
+
+def test_paged_and_dense_caches_agree_bit_for_bit():
+    """Same rows, same tiles, same order of operations: only the addresses differ."""
+    B, H, Hkv, D, block_rows, lens = 2, 4, 2, 128, 128, [1000, 513]
+    q = make_qkv(B, H, 1, D, "bf16", seed=95)[0].cuda()
+    _, k, v = (t.cuda() for t in make_qkv(B, Hkv, 1024, D, "bf16", seed=96))
+    lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    dense = binding.sdpa_kv(q, k, v, kv_lens=lens_d, splits=4)
+    # pages in reverse order of the dense blocks
+    nb = 1024 // block_rows
+    kp = k.view(B, Hkv, nb, block_rows, D).permute(0, 2, 1, 3, 4).reshape(B * nb, Hkv, block_rows, D).flip(0).contiguous()
+    vp = v.view(B, Hkv, nb, block_rows, D).permute(0, 2, 1, 3, 4).reshape(B * nb, Hkv, block_rows, D).flip(0).contiguous()
+    table = (B * nb - 1 - torch.arange(B * nb, dtype=torch.int32, device="cuda")).view(B, nb).contiguous()
+    paged = binding.sdpa_paged(q, kp, vp, lens_d, table, splits=4)
+    torch.cuda.synchronize()
+    assert torch.equal(dense, paged)
