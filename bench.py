@@ -72,6 +72,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    ap.add_argument("--sweep-tiles", action="store_true",
+                    help="also time every legal (T_M, T_N) of the workload (the schedule knobs of the paper's Table 1)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only ceiling measurement")
     ap.add_argument("--input-fill", default="normal", choices=["normal", "zeros", "ones"],
                     help="normal = the seeded workload; zeros / ones = same shapes with constant data "
@@ -465,6 +467,20 @@ def main():
         out["frac_of_mfma_only_ceiling_random_operands"] = round(kern_tflops / ceil["random_operands"], 4)
         out["frac_of_loop_mix_ceiling"] = round(kern_tflops / ceil["random_operands_plus_loop_mix"], 4)
         out["hbm_copy_ceiling_GBs"] = hbm_copy_ceiling(torch)
+
+    if args.sweep_tiles:
+        sweep = {}
+        for tm_ in (64, 128):
+            for tn_ in (32, 64, 128):
+                if tn_ == 128 and w.D != 64:
+                    sweep[f"{tm_}x{tn_}"] = "not offered at this head dim (register budget)"
+                    continue
+                rr = time_workload(pkg, torch, args.workload, args.dtype, max(10, args.steps // 2), 3, (tm_, tn_), flags,
+                                   args.input_fill, shape, args.qk_std)
+                tf = flops / (rr["kernel_ms_avg"] * 1e-3) / 1e12
+                sweep[f"{tm_}x{tn_}"] = {"kernel_ms_avg": round(rr["kernel_ms_avg"], 5), "tflops": round(tf, 2),
+                                         "frac_of_mfma_peak": round(tf / PEAK_MFMA_TFLOPS, 4)}
+        out["tile_sweep"] = sweep
 
     if args.all_workloads:
         others = {}

@@ -225,7 +225,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
     // (a cache entry shorter than the query block leaves the first rows without any key: reach < 0)
     const int reach = pos_hi + koff;
-    const int nTw = causal ? (reach < 0 ? 0 : reach / TN + 1) : nT;
+    const int nTw = causal ? ((KV && reach < 0) ? 0 : reach / TN + 1) : nT;
     const int klim = causal ? pos_own + koff : Skv - 1;
     const int nfull = ((causal ? pos_lo + koff : Skv - 1) + 1) / TN;
     // this workgroup's run of tiles [t0, t1): all nTw of them unless the key range is split
@@ -500,9 +500,11 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         return;
     }
     // a row that no key reaches (empty cache entry, causal limit before the first key) has l = 0: O = 0, LSE = -inf
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    // (only the cache variants can have such a row: in the square problem every row sees key 0)
+    const bool no_key = KV && !(l_tot > 0.f);
+    const float inv = no_key ? 0.f : 1.0f / l_tot;
     if (lse != nullptr && g == 0 && qrow < S)
-        lse[(size_t)head * S + qrow] = l_tot > 0.f ? (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f : -INFINITY;
+        lse[(size_t)head * S + qrow] = no_key ? -INFINITY : (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     // (the launcher sizes the dynamic LDS for the larger of the tile slots and this staging area)
     {
         constexpr int CMASK = CPR - 1;                // chunks per row is 8 or 16
