@@ -72,6 +72,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
     ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    ap.add_argument("--tune", action="store_true",
+                    help="pick the tile with tiled_sdpa_tune_tile (outside the timed region) instead of the heuristic")
     ap.add_argument("--sweep-tiles", action="store_true",
                     help="also time every legal (T_M, T_N) of the workload (the schedule knobs of the paper's Table 1)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only ceiling measurement")
@@ -419,6 +421,17 @@ def main():
         bench_bwd(pkg, torch, args, flags)
         return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    tuned = None
+    if args.tune and tile is None:
+        # schedule search on the workload's own tensors, before and outside the timed region
+        from paper_2603_01960_amd.workloads import make_qkv, make_workload
+        if shape is not None:
+            tq, tk, tv = make_qkv(*shape, args.dtype or "bf16", 4242)
+        else:
+            _, tq, tk, tv = make_workload(args.workload, args.dtype)
+        tile, times = pkg.tune_tile(tq.cuda(), tk.cuda(), tv.cuda(), causal=args.causal, launches=20, flags=flags)
+        tuned = {f"{a}x{b}": round(t, 5) for (a, b), t in times.items()}
+        del tq, tk, tv
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape, args.qk_std)
     w, dtype = r["workload"], r["dtype"]
     flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
@@ -461,6 +474,9 @@ def main():
                 "library_version": pkg.version(), "host": platform.processor() or platform.machine()},
     }
 
+    if tuned is not None:
+        out["config"]["tile_chosen_by"] = "tiled_sdpa_tune_tile (20 launches per candidate)"
+        out["config"]["tune_ms_per_launch"] = tuned
     if not args.no_ceilings:
         ceil = mfma_ceilings(pkg, torch, dtype)
         out["mfma_only_ceiling_tflops"] = ceil

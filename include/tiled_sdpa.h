@@ -97,6 +97,23 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
 int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flags, int *tile_m, int *tile_n);
 
 /*
+ * Schedule search (the tuning policy of Sections 4.2.2-4.2.3: a small set of tile candidates, the
+ * best one kept per problem shape): runs the forward pass of tiled_sdpa_fwd_ex with every legal
+ * (tile_m, tile_n) on the caller's tensors -- one untimed launch, then `launches` (1..1000) timed
+ * ones between two HIP events on `stream` -- and reports the fastest in *tile_m, *tile_n.  Unlike
+ * every other entry point this one WAITS for the stream (once per candidate); it keeps no record, the
+ * caller passes the result to tiled_sdpa_fwd_ex.  o is overwritten (with the correct result).
+ * ms_per_launch: NULL, or host array of 6 floats that receives the time per launch of
+ * (64,32) (64,64) (64,128) (128,32) (128,64) (128,128) in that order, -1 for a tile that is not
+ * offered at this D.  An empty problem returns the heuristic's tile and measures nothing.
+ * Validation as tiled_sdpa_fwd_ex; launches out of range is TSDPA_ERR_BAD_SHAPE; tile_m or tile_n
+ * NULL is TSDPA_ERR_NULL_PTR.  Timings are only meaningful on an otherwise idle GPU (Section 4.2.3).
+ */
+int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
+                         int B, int H, int S, int D, float scale, int dtype, void *stream, unsigned flags,
+                         int launches, int *tile_m, int *tile_n, float *ms_per_launch);
+
+/*
  * Forward pass for Sq query rows against Skv key/value rows, with the key range optionally split
  * over several workgroups: the KV-cache / decoding shapes that the paper names as future work
  * (Section 8), and the cure for shapes whose B*H*ceil(Sq/tile_m) workgroups cannot fill the GPU.

@@ -25,6 +25,7 @@ EXPORTS = (
     "tiled_sdpa_bwd",
     "tiled_sdpa_bwd_workspace_bytes",
     "tiled_sdpa_default_tile",
+    "tiled_sdpa_tune_tile",
     "tiled_sdpa_fwd_kv",
     "tiled_sdpa_fwd_gqa",
     "tiled_sdpa_fwd_kvcache",
@@ -78,6 +79,9 @@ def load_library():
     lib.tiled_sdpa_fwd_kvcache.argtypes = [vp] * 6 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_fwd_paged.restype = ci
     lib.tiled_sdpa_fwd_paged.argtypes = [vp] * 7 + [ci] * 7 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
+    lib.tiled_sdpa_tune_tile.restype = ci
+    lib.tiled_sdpa_tune_tile.argtypes = [vp] * 4 + [ci] * 4 + [cf, ci, vp, ctypes.c_uint, ci,
+                                         ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(cf)]
     lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
@@ -97,6 +101,37 @@ def version() -> int:
 
 def status_string(status: int) -> str:
     return load_library().tiled_sdpa_status_string(int(status)).decode()
+
+
+TILE_ORDER = ((64, 32), (64, 64), (64, 128), (128, 32), (128, 64), (128, 128))
+
+
+def tune_tile(q, k, v, causal: bool = False, scale=None, *, launches: int = 10, flags: int = 0):
+    """Time every legal (T_M, T_N) on these tensors (tiled_sdpa_tune_tile; waits for the stream) and
+    return ``((tile_m, tile_n), {tile: ms per launch})``.  Pass the tile to :func:`sdpa`."""
+    import torch
+
+    if causal:
+        flags |= FLAG_CAUSAL
+    for t in (q, k, v):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dim() != 4 or not t.is_contiguous():
+            raise ValueError("q, k, v must be contiguous [B, H, S, D] device tensors")
+    if q.dtype not in (torch.float16, torch.bfloat16) or k.dtype != q.dtype or v.dtype != q.dtype or \
+            k.shape != q.shape or v.shape != q.shape:
+        raise ValueError("q, k, v must share shape and dtype float16 or bfloat16")
+    B, H, S, D = q.shape
+    out = torch.empty_like(q)
+    tm, tn = ctypes.c_int(0), ctypes.c_int(0)
+    ms = (ctypes.c_float * 6)()
+    guard, stream = _guard_and_stream(torch, q.device)
+    with guard:
+        st = load_library().tiled_sdpa_tune_tile(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, S, D,
+                                                 math.nan if scale is None else float(scale),
+                                                 F16 if q.dtype == torch.float16 else BF16, stream, flags, launches,
+                                                 ctypes.byref(tm), ctypes.byref(tn), ms)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return (tm.value, tn.value), {t: float(x) for t, x in zip(TILE_ORDER, ms) if x >= 0}
 
 
 def default_tile(B: int, H: int, S: int, D: int, dtype: int, flags: int = 0):

@@ -133,6 +133,49 @@ int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flag
     return TSDPA_OK;
 }
 
+int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
+                         int B, int H, int S, int D, float scale, int dtype, void *stream, unsigned flags,
+                         int launches, int *tile_m, int *tile_n, float *ms_per_launch)
+{
+    if (!tile_m || !tile_n) return TSDPA_ERR_NULL_PTR;
+    if (launches < 1 || launches > 1000) return TSDPA_ERR_BAD_SHAPE;
+    int st = validate_shape(B, H, S, D, dtype);
+    if (st != TSDPA_OK) return st;
+    pick_tile(B * H, S, D, (flags & TSDPA_FLAG_CAUSAL) != 0, tile_m, tile_n);
+    if (ms_per_launch)
+        for (int i = 0; i < 6; ++i) ms_per_launch[i] = -1.0f;
+    if ((int64_t)B * H * S == 0) return TSDPA_OK;
+    if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
+    if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15u) != 0) return TSDPA_ERR_MISALIGNED;
+    if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return TSDPA_ERR_LAUNCH;
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return TSDPA_ERR_LAUNCH; }
+    static const int tms[2] = {64, 128}, tns[3] = {32, 64, 128};
+    float best = -1.0f;
+    st = TSDPA_OK;
+    for (int i = 0; i < 6 && st == TSDPA_OK; ++i) {
+        const int tm = tms[i / 3], tn = tns[i % 3];
+        if (!valid_tile(tm, tn, D)) continue;
+        // one untimed launch (first use of an instantiation sets its attributes), then the timed run
+        st = tiled_sdpa_fwd_ex(q, k, v, o, nullptr, B, H, S, D, scale, dtype, stream, tm, tn, flags);
+        if (st != TSDPA_OK) break;
+        if (hipEventRecord(e0, (hipStream_t)stream) != hipSuccess) { st = TSDPA_ERR_LAUNCH; break; }
+        for (int r = 0; r < launches && st == TSDPA_OK; ++r)
+            st = tiled_sdpa_fwd_ex(q, k, v, o, nullptr, B, H, S, D, scale, dtype, stream, tm, tn, flags);
+        if (st != TSDPA_OK) break;
+        float ms = 0.0f;
+        if (hipEventRecord(e1, (hipStream_t)stream) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+            hipEventElapsedTime(&ms, e0, e1) != hipSuccess) { st = TSDPA_ERR_LAUNCH; break; }
+        ms /= (float)launches;
+        if (ms_per_launch) ms_per_launch[i] = ms;
+        if (best < 0.0f || ms < best) { best = ms; *tile_m = tm; *tile_n = tn; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return st;
+}
+
 int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
                       int B, int H, int S, int D, float scale, int dtype, void *stream,
                       int tile_m, int tile_n, unsigned flags)

@@ -195,6 +195,22 @@ def test_paged_entry_point_validation(lib, kwargs, expect):
     assert st == expect, binding.status_string(st)
 
 
+def test_tune_entry_point_validation(lib):
+    tm, tn = ctypes.c_int(-1), ctypes.c_int(-1)
+    ms = (ctypes.c_float * 6)(*([7.0] * 6))
+    call = lambda **kw: lib.tiled_sdpa_tune_tile(kw.get("q", P), P, P, P, kw.get("B", 2), 4, kw.get("S", 300), kw.get("D", 64),
+                                                 0.125, kw.get("dtype", 1), None, 0, kw.get("launches", 5),
+                                                 kw.get("tm", ctypes.byref(tm)), ctypes.byref(tn), ms)
+    assert call(tm=None) == NULL
+    assert call(launches=0) == SHAPE and call(launches=1001) == SHAPE
+    assert call(dtype=4) == DTYPE and call(D=72) == BAD_D and call(S=-1) == SHAPE
+    # an empty problem measures nothing and reports the heuristic's tile
+    assert call(B=0) == OK
+    assert (tm.value, tn.value) == binding.default_tile(0, 4, 300, 64, binding.BF16)
+    assert all(x == -1.0 for x in ms)
+    assert call(q=None) == NULL                     # reached through the forward entry point's own checks
+
+
 def test_kv_workspace_size_and_default_splits(lib):
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 1) == 0
     assert binding.kv_workspace_bytes(2, 4, 5, 64, 0) == 0

@@ -378,3 +378,19 @@ def test_config_C4_sampled_rows_tile_sweep():
 
 def test_config_C5_sampled_rows():
     _long_config("C5", [None, (64, 32), (128, 64)])
+
+
+def test_schedule_search_returns_a_legal_tile_and_its_timings():
+    for D, dtype, n_tiles in ((128, "bf16", 4), (64, "f16", 6)):
+        q, k, v = (t.cuda() for t in make_qkv(2, 4, 700, D, dtype, seed=33))
+        tile, times = binding.tune_tile(q, k, v, causal=(D == 64), launches=3)
+        say(f"[case] tune D={D} {dtype}: {tile} {times}")
+        assert tile in times and len(times) == n_tiles
+        assert all(0 < t < 100 for t in times.values())
+        assert times[tile] == min(times.values())
+        assert legal(tile, D)
+        # the tile it reports gives the same result as any other
+        a = binding.sdpa(q, k, v, causal=(D == 64), tile=tile)
+        b = binding.sdpa(q, k, v, causal=(D == 64))
+        torch.cuda.synchronize()
+        assert float((a.float() - b.float()).abs().max()) <= TOL[dtype]
