@@ -238,6 +238,28 @@ def sdpa_bwd(q, k, v, dout, scale=None, causal=False, qrows=None, krows=None):
     return dq.reshape(*lead, nq, D), dk.reshape(*lead, nk, D), dv.reshape(*lead, nk, D)
 
 
+def sdpa_bwd_grouped(q, k, v, dout, scale=None, causal=False, qrows=None, krows=None):
+    """Backward pass with grouped heads: q, dout [B, H, S, D], k, v [B, Hkv, S, D], H = G * Hkv, query head h
+    reading key/value head h // G (the paper has G = 1, Section 3.1).  The forward pass is Eq. 1 per query
+    head on the key/value rows of its group, i.e. on K and V repeated G times along the head axis, so by the
+    chain rule of that repetition dQ is the gradient of the repeated problem and dK, dV are its gradients
+    summed over the G query heads of each group.  That is what is computed here, literally, with
+    :func:`sdpa_bwd` (the pinned row-by-row routine) on the repeated tensors.
+
+    Returns (dq [B, H, nq, D], dk [B, Hkv, nk, D], dv [B, Hkv, nk, D])."""
+    q32, k32, v32 = _as_f32(q), _as_f32(k), _as_f32(v)
+    if q32.ndim != 4 or k32.ndim != 4 or k32.shape != v32.shape or q32.shape[0] != k32.shape[0] or \
+            q32.shape[2:] != k32.shape[2:] or k32.shape[1] == 0 or q32.shape[1] % k32.shape[1] != 0:
+        raise ValueError("q must be [B, H, S, D] and k, v [B, Hkv, S, D] with H a multiple of Hkv")
+    B, H, S, D = q32.shape
+    Hkv = k32.shape[1]
+    G = H // Hkv
+    dq, dkx, dvx = sdpa_bwd(q32, np.repeat(k32, G, axis=1), np.repeat(v32, G, axis=1), dout,
+                            scale=scale, causal=causal, qrows=qrows, krows=krows)
+    nk = dkx.shape[2]
+    return dq, dkx.reshape(B, Hkv, G, nk, D).sum(axis=2), dvx.reshape(B, Hkv, G, nk, D).sum(axis=2)
+
+
 def sdpa_bwd_numpy(q, k, v, dout, scale=None, causal=False):
     """The same gradients as numpy float64 matrix expressions (small shapes): with P the row softmax
     of the scaled, masked scores, dV = P^T dO, dP = dO V^T, dS = P * (dP - rowsum(P * dP)),

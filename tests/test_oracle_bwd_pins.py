@@ -269,3 +269,72 @@ def test_backward_pins_pass_on_the_oracle_and_catch_planted_mistakes():
     for name, kw in mutants.items():
         bad = _bwd_pin_suite(lambda q, k, v, do, s, kw=kw: _formulas(q, k, v, do, s, **kw))
         assert bad, f"planted mistake not caught: {name}"
+
+
+# ------------------------------------------------------------------ grouped heads
+def _grouped_inputs(B, H, Hkv, S, D, seed):
+    rng = np.random.default_rng(seed)
+    f = lambda *shape: rng.standard_normal(shape).astype(np.float32)
+    return f(B, H, S, D), f(B, Hkv, S, D), f(B, Hkv, S, D), f(B, H, S, D)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("B,H,Hkv,S,D", [(2, 4, 2, 7, 8), (1, 6, 1, 5, 4), (1, 3, 3, 9, 16)])
+def test_grouped_backward_matches_torch_autograd_through_repeat_interleave(B, H, Hkv, S, D, causal):
+    """Independent path: torch float64 autograd differentiates through the head repetition itself."""
+    torch = pytest.importorskip("torch")
+    q, k, v, do = _grouped_inputs(B, H, Hkv, S, D, seed=40 + S)
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (q, k, v))
+    G = H // Hkv
+    o = torch.nn.functional.scaled_dot_product_attention(tq, tk.repeat_interleave(G, dim=1),
+                                                         tv.repeat_interleave(G, dim=1), is_causal=causal,
+                                                         scale=float(np.float32(1.0 / np.sqrt(D))))   # the oracle's default, as the float32 the device gets
+    (o * torch.tensor(do, dtype=torch.float64)).sum().backward()
+    dq, dk, dv = orc.sdpa_bwd_grouped(q, k, v, do, causal=causal)
+    for got, want in ((dq, tq.grad), (dk, tk.grad), (dv, tv.grad)):
+        np.testing.assert_allclose(got, want.numpy(), rtol=1e-10, atol=1e-12)
+
+
+def test_grouped_backward_against_finite_differences_of_the_forward_definition():
+    """Perturbing one key/value element moves the outputs of all G query heads of its group."""
+    B, H, Hkv, S, D, G = 1, 4, 2, 5, 3, 2
+    q, k, v, do = _grouped_inputs(B, H, Hkv, S, D, seed=77)
+    scale = 0.4
+
+    def loss(k_, v_):
+        o = orc.sdpa(q, np.repeat(k_, G, axis=1), np.repeat(v_, G, axis=1), scale=scale, causal=True)
+        return float((o * do.astype(np.float64)).sum())
+
+    dq, dk, dv = orc.sdpa_bwd_grouped(q, k, v, do, scale=scale, causal=True)
+    eps = 2.0 ** -9                    # exactly representable steps on float32 inputs
+    for (h, j, d) in ((0, 0, 0), (1, 3, 2), (0, 4, 1)):
+        for which, grad in (("k", dk), ("v", dv)):
+            kp, km, vp, vm = k.copy(), k.copy(), v.copy(), v.copy()
+            (kp if which == "k" else vp)[0, h, j, d] += eps
+            (km if which == "k" else vm)[0, h, j, d] -= eps
+            fd = (loss(kp, vp) - loss(km, vm)) / (2 * eps)
+            assert abs(fd - grad[0, h, j, d]) <= 1e-5 * max(1.0, abs(fd)), (which, h, j, d, fd, grad[0, h, j, d])
+
+
+def test_grouped_backward_special_cases_and_row_subsets():
+    q, k, v, do = _grouped_inputs(2, 4, 2, 6, 8, seed=5)
+    # one query head per key/value head: the plain backward pass
+    a = orc.sdpa_bwd_grouped(q[:, :2], k, v, do[:, :2], causal=True)
+    b = orc.sdpa_bwd(q[:, :2], k, v, do[:, :2], causal=True)
+    for x, y in zip(a, b):
+        np.testing.assert_array_equal(x, y)
+    # identical query heads in a group (same q, same dout): dK, dV are G times one head's
+    q2, do2 = np.repeat(q[:, :2], 2, axis=1), np.repeat(do[:, :2], 2, axis=1)      # heads (0,0,1,1) over 2 kv heads
+    dq2, dk2, dv2 = orc.sdpa_bwd_grouped(q2, k, v, do2)
+    _, dk1, dv1 = orc.sdpa_bwd(q[:, :2], k, v, do[:, :2])
+    np.testing.assert_allclose(dk2, 2 * dk1, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(dv2, 2 * dv1, rtol=1e-13, atol=1e-15)
+    np.testing.assert_array_equal(dq2[:, 0], dq2[:, 1])
+    # row subsets select rows of the full result
+    full = orc.sdpa_bwd_grouped(q, k, v, do, causal=True)
+    sub = orc.sdpa_bwd_grouped(q, k, v, do, causal=True, qrows=[0, 5], krows=[1, 2, 4])
+    np.testing.assert_array_equal(sub[0], full[0][:, :, [0, 5]])
+    np.testing.assert_array_equal(sub[1], full[1][:, :, [1, 2, 4]])
+    np.testing.assert_array_equal(sub[2], full[2][:, :, [1, 2, 4]])
+    with pytest.raises(ValueError):
+        orc.sdpa_bwd_grouped(q[:, :3], k, v, do[:, :3])
