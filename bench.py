@@ -332,11 +332,14 @@ def bench_bwd(pkg, torch, args, flags):
         w, q, k, v = make_workload(args.workload, args.dtype)
         dtype = args.dtype or w.dtypes[0]
     causal = bool(flags & pkg.binding.FLAG_CAUSAL)
+    Hkv = args.kv_heads or w.H
+    if Hkv != w.H:          # grouped heads: the first Hkv heads of the seeded K and V serve as the key/value heads
+        k, v = k[:, :Hkv].contiguous(), v[:, :Hkv].contiguous()
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     g = torch.Generator(device="cpu").manual_seed(w.seed + 50)
     dout = torch.randn(*q.shape, dtype=torch.float32, generator=g).to(q.dtype).cuda()
-    o, lse = pkg.sdpa(qd, kd, vd, causal=causal, return_lse=True)
-    grads = tuple(torch.empty_like(qd) for _ in range(3))
+    o, lse = pkg.sdpa_kv(qd, kd, vd, causal=causal, return_lse=True) if Hkv != w.H else pkg.sdpa(qd, kd, vd, causal=causal, return_lse=True)
+    grads = (torch.empty_like(qd), torch.empty_like(kd), torch.empty_like(kd))
     ws = torch.empty(pkg.bwd_workspace_bytes(w.B, w.H, w.S), dtype=torch.uint8, device="cuda")
     run = lambda: pkg.sdpa_backward(qd, kd, vd, o, dout, lse, causal=causal, workspace=ws, grads=grads)
     for _ in range(args.warmup):
@@ -359,7 +362,8 @@ def bench_bwd(pkg, torch, args, flags):
         "metric": "SDPA backward TFLOP/s (10*B*H*S^2*D / t)", "value": round(flops / (wall_ms * 1e-3) / 1e12, 2),
         "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall_ms, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: SDPA bwd {'causal' if causal else 'non-causal'} B={w.B} H={w.H} S={w.S} D={w.D} {dtype}"},
+        "config": {"workload": f"{w.name}: SDPA bwd {'causal' if causal else 'non-causal'} B={w.B} H={w.H}"
+                               f"{'' if Hkv == w.H else f' (kv heads {Hkv})'} S={w.S} D={w.D} {dtype}"},
         "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf / PEAK_MFMA_TFLOPS, 4), "traffic": None,
                      "kernel": ("sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dK+dV> + sdpa_bwd_kernel<dQ>" if w.D == 64 else

@@ -254,6 +254,21 @@ int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, c
                    int B, int H, int S, int D, float scale, int dtype, unsigned flags,
                    void *workspace, unsigned long long workspace_bytes, void *stream);
 
+/*
+ * tiled_sdpa_bwd with grouped heads (the backward pass of tiled_sdpa_fwd_gqa at Sq = Skv = S): H query
+ * heads read Hkv key/value heads, query head h the head h / (H / Hkv).  q, o, dout, dq : [B, H, S, D];
+ * lse : [B, H, S];  k, v, dk, dv : [B, Hkv, S, D].  dq is the gradient of each query head against the
+ * keys and values of its group; dk and dv are the gradients summed over the query heads of the group
+ * (the chain rule of sharing one head among them), accumulated in FP32 inside one workgroup per
+ * (key/value head, key tile), in a fixed order: results are deterministic.  Workspace as for
+ * tiled_sdpa_bwd(B, H, S).  Everything else, validation included, as tiled_sdpa_bwd, which is this call
+ * with Hkv = H; Hkv <= 0 with H > 0 or H not a multiple of Hkv is TSDPA_ERR_BAD_SHAPE.
+ */
+int tiled_sdpa_bwd_gqa(const void *q, const void *k, const void *v, const void *o, const void *dout,
+                       const float *lse, void *dq, void *dk, void *dv,
+                       int B, int H, int Hkv, int S, int D, float scale, int dtype, unsigned flags,
+                       void *workspace, unsigned long long workspace_bytes, void *stream);
+
 /* Workspace bytes tiled_sdpa_bwd needs: 2 * (B*H*S + 128) floats.  0 for negative arguments. */
 unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S);
 

@@ -23,6 +23,7 @@ EXPORTS = (
     "tiled_sdpa_fwd",
     "tiled_sdpa_fwd_ex",
     "tiled_sdpa_bwd",
+    "tiled_sdpa_bwd_gqa",
     "tiled_sdpa_bwd_workspace_bytes",
     "tiled_sdpa_default_tile",
     "tiled_sdpa_tune_tile",
@@ -83,6 +84,8 @@ def load_library():
     lib.tiled_sdpa_tune_tile.argtypes = [vp] * 4 + [ci] * 4 + [cf, ci, vp, ctypes.c_uint, ci,
                                          ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(cf)]
     lib.tiled_sdpa_bwd.argtypes = [vp] * 9 + [ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
+    lib.tiled_sdpa_bwd_gqa.restype = ci
+    lib.tiled_sdpa_bwd_gqa.argtypes = [vp] * 9 + [ci, ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
     lib.tiled_sdpa_probe_mfma.restype = ci
@@ -366,37 +369,44 @@ def tiled_sdpa_bwd(q_ptr, k_ptr, v_ptr, o_ptr, dout_ptr, lse_ptr, dq_ptr, dk_ptr
 def sdpa_backward(q, k, v, o, dout, lse, causal: bool = False, scale=None, *, workspace=None, grads=None):
     """(dq, dk, dv) for the attention of :func:`sdpa`; ``o`` and ``lse`` are that call's outputs
     (``return_lse=True``) for the same q, k, v, causal and scale.  ``grads=(dq, dk, dv)`` and
-    ``workspace`` let the caller own the buffers; otherwise torch allocates them."""
+    ``workspace`` let the caller own the buffers; otherwise torch allocates them.
+
+    Grouped heads: k, v [B, Hkv, S, D] with H a multiple of Hkv (the forward of ``sdpa_kv`` at Sq = Skv);
+    dk, dv then have the shape of k and hold the sum over the query heads of each group."""
     import torch
 
-    for name, t in (("q", q), ("k", k), ("v", v), ("o", o), ("dout", dout)):
+    for name, t, like in (("q", q, q), ("k", k, k), ("v", v, k), ("o", o, q), ("dout", dout, q)):
         if not isinstance(t, torch.Tensor) or not t.is_cuda:
             raise ValueError(f"{name} must be a device tensor")
         if t.dim() != 4 or not t.is_contiguous():
             raise ValueError(f"{name} must be contiguous [B, H, S, D]")
-        if t.shape != q.shape or t.dtype != q.dtype or t.device != q.device:
-            raise ValueError("q, k, v, o, dout must agree in shape, dtype and device")
+        if t.shape != like.shape or t.dtype != q.dtype or t.device != q.device:
+            raise ValueError("q, o, dout and k, v must agree in shape, dtype and device")
     if q.dtype not in (torch.float16, torch.bfloat16):
         raise ValueError("dtype must be float16 or bfloat16")
     B, H, S, D = q.shape
+    Hkv = k.shape[1]
+    if k.shape[0] != B or k.shape[2:] != q.shape[2:] or Hkv == 0 or H % Hkv != 0:
+        raise ValueError("k, v must be [B, Hkv, S, D] with H a multiple of Hkv")
     if lse.shape != (B, H, S) or lse.dtype != torch.float32 or not lse.is_contiguous() or lse.device != q.device:
         raise ValueError("lse must be contiguous float32 [B, H, S] on the same device")
     dtype = F16 if q.dtype == torch.float16 else BF16
     if grads is None:
-        grads = (torch.empty_like(q), torch.empty_like(q), torch.empty_like(q))
-    for gname, t in zip(("dq", "dk", "dv"), grads):
-        if t.shape != q.shape or t.dtype != q.dtype or not t.is_contiguous() or t.device != q.device:
-            raise ValueError(f"{gname} must match q in shape, dtype, device and be contiguous")
+        grads = (torch.empty_like(q), torch.empty_like(k), torch.empty_like(k))
+    for gname, t, like in zip(("dq", "dk", "dv"), grads, (q, k, k)):
+        if t.shape != like.shape or t.dtype != q.dtype or not t.is_contiguous() or t.device != q.device:
+            raise ValueError(f"{gname} must match {'q' if like is q else 'k'} in shape, dtype, device and be contiguous")
     need = bwd_workspace_bytes(B, H, S)
     if workspace is None:
         workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
     ws_bytes = workspace.numel() * workspace.element_size()
     guard, stream = _guard_and_stream(torch, q.device)
     with guard:
-        st = tiled_sdpa_bwd(q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), dout.data_ptr(),
-                            lse.data_ptr(), grads[0].data_ptr(), grads[1].data_ptr(), grads[2].data_ptr(),
-                            B, H, S, D, math.nan if scale is None else scale, dtype,
-                            FLAG_CAUSAL if causal else 0, workspace.data_ptr(), ws_bytes, stream)
+        st = int(load_library().tiled_sdpa_bwd_gqa(
+            q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), dout.data_ptr(),
+            lse.data_ptr(), grads[0].data_ptr(), grads[1].data_ptr(), grads[2].data_ptr(),
+            B, H, Hkv, S, D, math.nan if scale is None else float(scale), dtype,
+            FLAG_CAUSAL if causal else 0, workspace.data_ptr(), ws_bytes, stream))
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return grads

@@ -19,12 +19,12 @@ template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS[4] = {2, 2, 
 template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {64, 32, 64, 32}; static constexpr bool FUSED_DKV = false; };
 template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {32, 32, 32, 32}; static constexpr bool FUSED_DKV = false; };   // 512-byte LDS rows
 
-template <typename T, int D, int MODE>
+template <typename T, int D, int MODE, bool GRP>
 int launch_bwd_pass(const BwdLaunchArgs &a)
 {
     using Sh = BwdShape<D>;
     constexpr int NW = Sh::NW, TS = Sh::TS[MODE], WPS = Sh::WPS[MODE];
-    auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, MODE>;
+    auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, MODE, GRP>;
     constexpr int lds_bytes = BwdGeom<D, TS>::LDS_BYTES;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -33,12 +33,28 @@ int launch_bwd_pass(const BwdLaunchArgs &a)
     });
     if (attr_err != hipSuccess) return (int)attr_err;
     const int nR = (a.S + NW * 32 - 1) / (NW * 32);
-    const int N = a.BH * nR;
+    // one workgroup per (head of the resident side, tile of its rows): query heads in the dQ pass, key/value heads otherwise
+    const int N = (MODE == BWD_DQ ? a.BH : a.BH / a.group) * nR;
     void *out = MODE == BWD_DQ ? a.dq : (MODE == BWD_DV ? a.dv : a.dk);
     hipLaunchKernelGGL(kern, dim3(N), dim3(NW * 64), lds_bytes, a.stream,
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.delta,
-                       (T *)out, (T *)(MODE == BWD_DKV ? a.dv : nullptr), a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes);
+                       (T *)out, (T *)(MODE == BWD_DKV ? a.dv : nullptr), a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes, a.group);
     return (int)hipGetLastError();
+}
+
+template <typename T, int D, bool GRP>
+int launch_bwd_passes(const BwdLaunchArgs &a)
+{
+    int err;
+    if constexpr (BwdShape<D>::FUSED_DKV) {
+        err = launch_bwd_pass<T, D, BWD_DKV, GRP>(a);
+    } else {
+        err = launch_bwd_pass<T, D, BWD_DV, GRP>(a);
+        if (err != 0) return err;
+        err = launch_bwd_pass<T, D, BWD_DK, GRP>(a);
+    }
+    if (err != 0) return err;
+    return launch_bwd_pass<T, D, BWD_DQ, GRP>(a);
 }
 
 template <typename T, int D>
@@ -50,15 +66,8 @@ int launch_bwd(const BwdLaunchArgs &a)
                        (const T *)a.o, (const T *)a.dout, a.lse, a.delta, a.lse2, rows);
     int err = (int)hipGetLastError();
     if (err != 0) return err;
-    if constexpr (BwdShape<D>::FUSED_DKV) {
-        err = launch_bwd_pass<T, D, BWD_DKV>(a);
-    } else {
-        err = launch_bwd_pass<T, D, BWD_DV>(a);
-        if (err != 0) return err;
-        err = launch_bwd_pass<T, D, BWD_DK>(a);
-    }
-    if (err != 0) return err;
-    return launch_bwd_pass<T, D, BWD_DQ>(a);
+    // one query head per key/value head keeps the kernels without the loop over a group
+    return a.group == 1 ? launch_bwd_passes<T, D, false>(a) : launch_bwd_passes<T, D, true>(a);
 }
 
 }  // namespace tsdpa

@@ -90,13 +90,19 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 // accumulators and both resident operand sets, which fits 256 registers per lane at D = 64 only.
 enum { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2, BWD_DKV = 3 };
 
-template <typename T, int D, int NW, int TS, int WPS, int MODE>
+// GRP: grouped heads, G query heads reading one key/value head (query head h the head h / G).  The
+// dQ pass then streams the K and V of its query head's group; the keys-resident passes run one
+// workgroup per (key/value head, key tile) and stream the Q and dO tiles of the G query heads of the
+// group one head after the other into the same accumulators, which is the sum over the group that dK
+// and dV are.  GRP = false is G = 1 with that loop gone.
+template <typename T, int D, int NW, int TS, int WPS, int MODE, bool GRP = false>
 __global__ void __launch_bounds__(NW * 64, WPS)
 sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                 const T *__restrict__ dout, const float *__restrict__ stats,   // Delta [B*H*S + slack], then LSE likewise
                 T *__restrict__ out,   // dQ, dK or dV
                 T *__restrict__ out2,  // dV of the fused dK + dV pass, else unused
-                int S, int nR, int N, float c, float scale, uint32_t rsign, int causal, unsigned stat_bytes)
+                int S, int nR, int N, float c, float scale, uint32_t rsign, int causal, unsigned stat_bytes,
+                int group)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     using E = Elem<T>;
@@ -121,14 +127,17 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const int g = lane >> 5, l32 = lane & 31;
 
     const int wg = remap_workgroup(blockIdx.x, N, false);
-    const int head = wg / nR;
+    const int head = wg / nR;                     // head of the resident side: a query head (dQ pass) or a key/value head
+    const int Gn = GRP ? group : 1;              // query heads per key/value head
     // causal: query tiles get longer with their index, key tiles shorter; start the long ones first
     const int rt = (causal && !KEYS_RES) ? nR - 1 - (wg - head * nR) : wg - head * nR;
     const size_t head_off = (size_t)head * (size_t)S * D;
     const T *r1 = (KEYS_RES ? k : q) + head_off;       // resident operands
     const T *r2 = (KEYS_RES ? v : dout) + head_off;
-    const T *t1 = (KEYS_RES ? q : k) + head_off;       // streamed operands
-    const T *t2 = (KEYS_RES ? dout : v) + head_off;
+    // streamed operands: the key/value head of this query head, or the first query head of this key/value head
+    const size_t shead0 = KEYS_RES ? (size_t)head * Gn : (size_t)(head / Gn);
+    const T *t1 = (KEYS_RES ? q : k) + shead0 * (size_t)S * D;
+    const T *t2 = (KEYS_RES ? dout : v) + shead0 * (size_t)S * D;
 
     // ---- resident rows as MFMA B-operands: lane holds R[row l32][kk*16 + g*8 .. +7]; the sign of a
     // negative scale is folded into R1 so that c = |scale| * log2(e) applies to the scores
@@ -166,14 +175,14 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
     for (int it = 0; it < NST; ++it) {
         const int e = it * 64 + lane;             // element of the tile's statistics block
-        stat_goff[it] = (e / TS == 0 ? (int)stat_bytes : 0) + (head * S + e % TS) * 4;
+        stat_goff[it] = (e / TS == 0 ? (int)stat_bytes : 0) + ((int)shead0 * S + e % TS) * 4;
     }
 
     // ---- streamed tiles HBM -> LDS, as in the forward kernel: a descriptor per tensor covers this
     // head's S rows (rows >= S read as zeros), lane `lane` of load `it` fills LDS chunk
     // (it*NW + wave)*64 + lane with the global chunk the swizzle maps there
-    const auto t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::GROW, 0x00020000);
-    const auto t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::GROW, 0x00020000);
+    auto t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::GROW, 0x00020000);
+    auto t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::GROW, 0x00020000);
     constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
     int goff[NLD];
 #pragma unroll
@@ -324,6 +333,17 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         if (!causal) return false;
         return KEYS_RES ? j * TS < r0 + RM - 1 : (j + 1) * TS - 1 > r0;
     };
+    for (int gq = 0; gq < (KEYS_RES ? Gn : 1); ++gq) {
+    if (GRP && KEYS_RES && gq > 0) {
+        // next query head of the group: its Q, dO and statistics (the last barrier of the previous head's
+        // loop has every wavefront past its last LDS read and every outstanding load landed)
+        t1 += (size_t)S * D;
+        t2 += (size_t)S * D;
+        t1_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t1, (short)0, S * G::GROW, 0x00020000);
+        t2_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)t2, (short)0, S * G::GROW, 0x00020000);
+#pragma unroll
+        for (int it = 0; it < NST; ++it) stat_goff[it] += S * 4;
+    }
     if (j0 < j1) {
         load_stats(j0, 0);
         load_tile(t1_rsrc, j0, lds);
@@ -343,6 +363,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 ++j;
             }
         }
+    }
     }
 
     // ---- store: out^T tiles are turned through LDS (as the forward kernel's O) and written as whole

@@ -37,7 +37,8 @@ struct BwdLaunchArgs {
     void *dq, *dk, *dv;
     float *delta, *lse2;     // workspace halves: [BH*S + slack] each
     unsigned stat_bytes;     // bytes of one workspace half
-    int BH, S;
+    int BH, S;               // query heads (B * H) and rows per head
+    int group;               // query heads per key/value head (1: k, v, dk, dv have BH heads too; else BH / group)
     float c;                 // |scale| * log2(e)
     float scale;             // signed scale: factor of dQ and dK
     uint32_t rsign;          // 0x80008000 when scale < 0 (sign folded into the resident Q or K), else 0

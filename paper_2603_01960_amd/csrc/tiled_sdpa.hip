@@ -397,9 +397,19 @@ int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, c
                    int B, int H, int S, int D, float scale, int dtype, unsigned flags,
                    void *workspace, unsigned long long workspace_bytes, void *stream)
 {
+    return tiled_sdpa_bwd_gqa(q, k, v, o, dout, lse, dq, dk, dv, B, H, H, S, D, scale, dtype, flags, workspace,
+                              workspace_bytes, stream);
+}
+
+int tiled_sdpa_bwd_gqa(const void *q, const void *k, const void *v, const void *o, const void *dout,
+                       const float *lse, void *dq, void *dk, void *dv,
+                       int B, int H, int Hkv, int S, int D, float scale, int dtype, unsigned flags,
+                       void *workspace, unsigned long long workspace_bytes, void *stream)
+{
     if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
     int st = validate_shape(B, H, S, D, dtype);
     if (st != TSDPA_OK) return st;
+    if (Hkv < 0 || (H > 0 && (Hkv == 0 || H % Hkv != 0))) return TSDPA_ERR_BAD_SHAPE;
     // the statistics arrays are addressed through a 32-bit byte range
     if ((int64_t)B * H * S >= ((int64_t)1 << 29)) return TSDPA_ERR_BAD_SHAPE;
     if ((int64_t)B * H * S == 0) return TSDPA_OK;
@@ -422,6 +432,7 @@ int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, c
     a.stat_bytes = (unsigned)(half * sizeof(float));
     a.BH = B * H;
     a.S = S;
+    a.group = H / Hkv;
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.scale = scale;
     a.rsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;

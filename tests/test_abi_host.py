@@ -195,6 +195,15 @@ def test_paged_entry_point_validation(lib, kwargs, expect):
     assert st == expect, binding.status_string(st)
 
 
+def test_grouped_backward_entry_point_validation(lib):
+    call = lambda **kw: lib.tiled_sdpa_bwd_gqa(kw.get("q", P), P, P, P, P, P, P, P, P, kw.get("B", 2), kw.get("H", 8),
+                                               kw.get("Hkv", 2), 100, kw.get("D", 64), 0.125, 1, 0, kw.get("ws", P), 1 << 20, None)
+    assert call(Hkv=3) == SHAPE and call(Hkv=0) == SHAPE and call(Hkv=-1) == SHAPE and call(Hkv=16) == SHAPE
+    assert call(D=72) == BAD_D
+    assert call(B=0) == OK and call(H=0, Hkv=0) == OK
+    assert call(q=None) == NULL and call(ws=None) == WORKSPACE
+
+
 def test_tune_entry_point_validation(lib):
     tm, tn = ctypes.c_int(-1), ctypes.c_int(-1)
     ms = (ctypes.c_float * 6)(*([7.0] * 6))

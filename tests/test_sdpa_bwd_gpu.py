@@ -187,3 +187,41 @@ def test_unsupported_head_dims_are_refused():
     with pytest.raises(binding.TiledSdpaError) as e:
         binding.sdpa_backward(x, x, x, x, x, lse)
     assert e.value.status == 4
+
+
+# ------------------------------------------------------------------ grouped heads
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("B,H,Hkv,S,D", [(2, 4, 2, 200, 64), (1, 8, 1, 333, 128), (1, 6, 2, 130, 96),
+                                         (1, 4, 2, 100, 160), (1, 4, 4, 70, 128), (2, 8, 2, 1, 64)])
+def test_grouped_heads(B, H, Hkv, S, D, dtype, causal):
+    """dK and dV are sums over the query heads of a group, taken inside one workgroup per key tile."""
+    q = make_qkv(B, H, S, D, dtype, seed=61)[0]
+    _, k, v = make_qkv(B, Hkv, S, D, dtype, seed=62)
+    do = make_dout(q.shape, dtype, 63)
+    say(f"[case] bwd grouped B={B} H={H} Hkv={Hkv} S={S} D={D} {dtype} causal={causal}")
+    qd, kd, vd, dd = (t.cuda() for t in (q, k, v, do))
+    o, lse = binding.sdpa_kv(qd, kd, vd, causal=causal, return_lse=True)
+    dq, dk, dv = binding.sdpa_backward(qd, kd, vd, o, dd, lse, causal=causal)
+    torch.cuda.synchronize()
+    assert dq.shape == q.shape and dk.shape == k.shape and dv.shape == v.shape
+    ref = orc.sdpa_bwd_grouped(q.float().numpy(), k.float().numpy(), v.float().numpy(), do.float().numpy(),
+                               causal=causal)
+    compare((dq.cpu(), dk.cpu(), dv.cpu()), ref, dtype, "grouped")
+
+
+def test_grouped_heads_at_a_long_sequence_on_sampled_rows():
+    B, H, Hkv, S, D, dtype = 1, 8, 2, 4096, 128, "bf16"
+    q = make_qkv(B, H, S, D, dtype, seed=64)[0]
+    _, k, v = make_qkv(B, Hkv, S, D, dtype, seed=65)
+    do = make_dout(q.shape, dtype, 66)
+    rows = sample_rows(S, limit=40)
+    for causal in (False, True):
+        say(f"[case] bwd grouped long S={S} causal={causal}")
+        qd, kd, vd, dd = (t.cuda() for t in (q, k, v, do))
+        o, lse = binding.sdpa_kv(qd, kd, vd, causal=causal, return_lse=True)
+        got = binding.sdpa_backward(qd, kd, vd, o, dd, lse, causal=causal)
+        torch.cuda.synchronize()
+        ref = orc.sdpa_bwd_grouped(q.float().numpy(), k.float().numpy(), v.float().numpy(), do.float().numpy(),
+                                   causal=causal, qrows=rows, krows=rows)
+        compare([g.cpu()[:, :, rows] for g in got], ref, dtype, "grouped long")
