@@ -301,3 +301,40 @@ def test_product_path_does_not_import_the_oracle():
     for path in list(pkg.glob("*.py")) + list((pkg / "csrc").glob("*")):
         text = path.read_text()
         assert "oracle" not in text.lower(), path
+
+
+def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
+    """The boundary is a C-ABI: the header must compile as C99 (and as C++), and a C program that only
+    knows the header must link against the library and get answers from the calls that need no GPU."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None or not binding.library_path().exists():
+        pytest.skip("gcc or the built library is missing")
+    src = tmp_path / "use.c"
+    src.write_text(
+        '#include <stdio.h>\n#include "tiled_sdpa.h"\n'
+        "int main(void) {\n"
+        "    int tm = 0, tn = 0, splits = 0;\n"
+        "    if (tiled_sdpa_version() < 100) return 1;\n"
+        "    if (tiled_sdpa_default_tile(2, 32, 8192, 128, TSDPA_BF16, 0u, &tm, &tn) != TSDPA_OK) return 2;\n"
+        "    if (tiled_sdpa_kv_default_splits(1, 8, 1, 16384, 128, TSDPA_BF16, 0u, &splits) != TSDPA_OK) return 3;\n"
+        "    if (tiled_sdpa_fwd(0, 0, 0, 0, 0, 2, 4, 100, 64, 0.125f, TSDPA_F16, 0) != TSDPA_ERR_NULL_PTR) return 4;\n"
+        "    if (tiled_sdpa_bwd_workspace_bytes(2, 4, 100) != 2ull * (2 * 4 * 100 + 128) * 4) return 5;\n"
+        '    printf("%d %d %d %s\\n", tm, tn, splits, tiled_sdpa_status_string(TSDPA_ERR_BAD_TILE));\n'
+        "    return 0;\n}\n")
+    inc = str(ROOT / "include")
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", f"-I{inc}", "-fsyntax-only", str(src)],
+                   check=True, capture_output=True)
+    gxx = shutil.which("g++")
+    if gxx:
+        subprocess.run([gxx, "-std=c++11", "-Wall", "-Werror", f"-I{inc}", "-fsyntax-only", "-x", "c++", str(src)],
+                       check=True, capture_output=True)
+    lib = binding.library_path()
+    exe = tmp_path / "use"
+    subprocess.run([gcc, "-std=c99", f"-I{inc}", str(src), "-o", str(exe), f"-L{lib.parent}", "-l:" + lib.name,
+                    f"-Wl,-rpath,{lib.parent}"], check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=120).stdout.split(maxsplit=3)
+    assert (int(out[0]), int(out[1])) == binding.default_tile(2, 32, 8192, 128, binding.BF16)
+    assert int(out[2]) == binding.kv_default_splits(1, 8, 1, 16384, 128, binding.BF16)
+    assert out[3].strip() == binding.status_string(6)
