@@ -214,6 +214,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // where tiles strictly above the diagonal of the workgroup's last row are neither read nor computed.
     const int nT = (Skv + TN - 1) / TN;
     const int r0 = qt * TM;
+    int page_now = 0, page_next = 0;              // paged cache: pages of the tile being loaded and of the one after it
     const int last_row = (r0 + TM < S ? r0 + TM : S) - 1;
     // least and greatest position among the workgroup's rows, and this lane's own
     int pos_lo = r0, pos_hi = last_row, pos_own = qrow_c;
@@ -263,9 +264,26 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             int valid = j < t1 ? Skv - row0 : 0;
             valid = valid < 0 ? 0 : (valid < TN ? valid : TN);
             const int blk = row0 >> block_shift;
-            const int page = pages[blk < max_blocks ? blk : 0];
+            // tiles are loaded in increasing order, K before V: the K load takes the page looked up while the
+            // previous tile was loaded and starts the lookup for the next tile, so that the scalar load's
+            // latency is not paid in front of every tile
+            if (tensor == k) {
+                page_now = page_next;
+                const int nblk = (row0 + TN) >> block_shift;
+                // (the value is the same in every lane; said explicitly, or the descriptor built from it is
+                // taken for lane-dependent and every load is wrapped in a loop over distinct descriptors)
+                page_next = nblk == blk ? page_now : __builtin_amdgcn_readfirstlane(pages[nblk < max_blocks ? nblk : 0]);
+            }
+            const int page = page_now;
             const size_t first = (((size_t)page * heads_per_batch + page_head) << block_shift) + (row0 - (blk << block_shift));
-            rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(tensor + first * D), (short)0, valid * G::GROW, 0x00020000);
+            // every input of the descriptor is the same in all lanes; stated for the two the compiler cannot
+            // see through (loaded values), or each load below becomes a loop over distinct descriptors
+            const unsigned long long byte0 = (unsigned long long)first * (unsigned long long)(D * sizeof(T));
+            const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)byte0);
+            const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(byte0 >> 32));
+            const char *base = (const char *)tensor + (((unsigned long long)hi << 32) | lo);
+            rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)base, (short)0,
+                                                     __builtin_amdgcn_readfirstlane(valid * G::GROW), 0x00020000);
             soff = 0;
         }
 #pragma unroll
@@ -428,6 +446,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
     // ahead cost 32 registers and measured 4 % slower).
     if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
+    if constexpr (PAGED) {
+        const int blk0 = (t0 * TN) >> block_shift;
+        page_next = __builtin_amdgcn_readfirstlane(pages[blk0 < max_blocks ? blk0 : 0]);
+    }
     load_tile(k, k_rsrc, k_goff, t0, lds + KSLOT0);
     load_tile(v, v_rsrc, v_goff, t0, lds + VSLOT0);
     TSDPA_WAIT_VMCNT0();
