@@ -41,7 +41,7 @@ int launch_one(const LaunchArgs &a)
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (T *)a.o, a.lse,
                        a.S, nQ, N, a.c, a.tau, a.qsign, a.linear_grid, a.causal,
                        a.Skv, a.splits, a.ws, a.rows_per_head, a.kv_lens, a.heads_per_batch,
-                       a.block_table, a.max_blocks, a.block_shift);
+                       a.block_table, a.max_blocks, a.block_shift, a.tile_rot);
     return (int)hipGetLastError();
 }
 

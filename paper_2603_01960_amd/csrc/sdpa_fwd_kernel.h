@@ -146,7 +146,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                 float tau, uint32_t qsign, int linear_grid, int causal,
                 int Skv_arg, int splits_arg, float *__restrict__ ws, int rows_per_head,
                 const int *__restrict__ kv_lens, int heads_per_batch,
-                const int *__restrict__ block_table, int max_blocks, int block_shift)
+                const int *__restrict__ block_table, int max_blocks, int block_shift, int tile_rot)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub; the body uses device-only types
     constexpr bool KV = KVM != 0, PAGED = KVM == 2;
@@ -445,22 +445,36 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // before the barrier that ended step j-1.  Overlap of matrix and vector work comes from the
     // wavefronts that share a SIMD (an in-wavefront software pipeline that ran the scores one tile
     // ahead cost 32 registers and measured 4 % slower).
+    // tiles below nfull need no mask: they run in pairs through the unmasked step; the few tiles
+    // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
+    // masked path, which is also correct for a tile that turns out to need no mask
+    const int fast_n = (t1 < nfull ? t1 : nfull) - t0;
+    const int fast_end = t0 + (fast_n > 0 ? fast_n & ~1 : 0);
+    // Dense cache with one query tile per head (decoding): every workgroup streams another head, and
+    // heads lie a power of two apart, so workgroups that all start at their tile 0 and advance in step
+    // keep hitting the same memory channels.  The order of the unmasked tiles is free (Eqs. 2-4 do not
+    // care), so each workgroup starts its sweep at a tile of its own and wraps around.
+    int rot = 0;
+    if constexpr (KVM == 1) {
+        const int nf = fast_end - t0;
+        if (tile_rot != 0 && nf > 2) rot = (int)((((unsigned)hs * 2654435761u) >> 12) % (unsigned)nf);
+    }
     if (!KV || t0 < t1) {   // a split past the diagonal has no tile: its state stays (o, m, l) = (0, -inf, 0)
     if constexpr (PAGED) {
         const int blk0 = (t0 * TN) >> block_shift;
         page_next = __builtin_amdgcn_readfirstlane(pages[blk0 < max_blocks ? blk0 : 0]);
     }
-    load_tile(k, k_rsrc, k_goff, t0, lds + KSLOT0);
-    load_tile(v, v_rsrc, v_goff, t0, lds + VSLOT0);
+    load_tile(k, k_rsrc, k_goff, t0 + rot, lds + KSLOT0);
+    load_tile(v, v_rsrc, v_goff, t0 + rot, lds + VSLOT0);
     TSDPA_WAIT_VMCNT0();
     __syncthreads();
 
-    // tile j: PAR = (j - t0) & 1 selects the slots, MASK the masked code path
-    auto step = [&](int j, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
+    // tile j, followed by tile jn: PAR (alternating) selects the slots, MASK the masked code path
+    auto step = [&](int j, int jn, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
-        if (j + 1 < t1) {
-            load_tile(k, k_rsrc, k_goff, j + 1, lds + (PAR ? KSLOT0 : KSLOT1));
-            load_tile(v, v_rsrc, v_goff, j + 1, lds + (PAR ? VSLOT0 : VSLOT1));
+        if (jn < t1) {
+            load_tile(k, k_rsrc, k_goff, jn, lds + (PAR ? KSLOT0 : KSLOT1));
+            load_tile(v, v_rsrc, v_goff, jn, lds + (PAR ? VSLOT0 : VSLOT1));
         }
         // the MFMAs of a step form chains fed by LDS reads: a raised wavefront priority lets them go
         // ahead of the other wavefronts' vector work whenever their operands are ready (+1-3 %), and
@@ -476,19 +490,29 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };
-    // tiles below nfull need no mask: they run in pairs through the unmasked step; the few tiles
-    // left (the diagonal band under the causal mask, the ragged tail, an odd one out) take the
-    // masked path, which is also correct for a tile that turns out to need no mask
-    const int fast_n = (t1 < nfull ? t1 : nfull) - t0;
-    const int fast_end = t0 + (fast_n > 0 ? fast_n & ~1 : 0);
     int j = t0;
-    for (; j < fast_end; j += 2) {
-        step(j, P0{}, std::false_type{});
-        step(j + 1, P1{}, std::false_type{});
+    if constexpr (KVM == 1) {
+        // unmasked tiles in rotated order: t0+rot ... fast_end-1, t0 ... t0+rot-1, then on to fast_end
+        int cur = t0 + rot;
+        for (; j < fast_end; j += 2) {
+            int n1 = cur + 1;
+            if (n1 == fast_end) n1 = t0;
+            int n2 = n1 + 1;
+            if (n2 == fast_end) n2 = t0;
+            if (j + 2 >= fast_end) n2 = fast_end;
+            step(cur, n1, P0{}, std::false_type{});
+            step(n1, n2, P1{}, std::false_type{});
+            cur = n2;
+        }
+    } else {
+        for (; j < fast_end; j += 2) {
+            step(j, j + 1, P0{}, std::false_type{});
+            step(j + 1, j + 2, P1{}, std::false_type{});
+        }
     }
     for (; j < t1; ++j) {
-        if ((j - t0) & 1) step(j, P1{}, std::true_type{});
-        else              step(j, P0{}, std::true_type{});
+        if ((j - t0) & 1) step(j, j + 1, P1{}, std::true_type{});
+        else              step(j, j + 1, P0{}, std::true_type{});
     }
     }
 

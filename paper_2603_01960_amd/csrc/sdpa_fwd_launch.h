@@ -23,6 +23,7 @@ struct LaunchArgs {
     int heads_per_batch;  // kv = 1: key/value heads per batch entry (head / heads_per_batch indexes kv_lens)
     const int *block_table; // kv = 1: NULL, or pages of a paged cache (device, int32 [B][max_blocks]); k, v are then [pages][heads_per_batch][1 << block_shift][D]
     int max_blocks, block_shift;
+    int tile_rot;      // kv = 1, dense cache: 1 = every workgroup starts its sweep over the unmasked tiles at a tile of its own
     int rows_per_head; // kv = 1: query positions per query head; S / rows_per_head query heads are folded into the S rows
     hipStream_t stream;
 };

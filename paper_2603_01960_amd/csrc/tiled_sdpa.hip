@@ -342,6 +342,7 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
     a.block_table = block_table;
     a.max_blocks = max_blocks;
     a.block_shift = block_shift;
+    a.tile_rot = (block_table == nullptr && rows <= tile_m) ? 1 : 0;    // one query tile per head: see the kernel
     a.c = std::fabs(scale) * 1.44269504088896340736f;
     a.tau = (flags & TSDPA_FLAG_EXACT_MAX) ? 0.0f : 8.0f;
     a.qsign = std::signbit(scale) && scale != 0.0f ? 0x80008000u : 0u;

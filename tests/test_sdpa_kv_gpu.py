@@ -389,17 +389,23 @@ def test_prefill_chunks_over_a_paged_cache(dtype, tile):
 
 
 def test_paged_and_dense_caches_agree_bit_for_bit():
-    """Same rows, same tiles, same order of operations: only the addresses differ."""
+    """Same rows, same tiles, same order of operations: only the addresses differ.  (With more than one
+    query tile per head; on a single one the dense path starts each workgroup's sweep at a tile of its
+    own, so there the two agree to rounding only.)"""
     B, H, Hkv, D, block_rows, lens = 2, 4, 2, 128, 128, [1000, 513]
-    q = make_qkv(B, H, 1, D, "bf16", seed=95)[0].cuda()
     _, k, v = (t.cuda() for t in make_qkv(B, Hkv, 1024, D, "bf16", seed=96))
     lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
-    dense = binding.sdpa_kv(q, k, v, kv_lens=lens_d, splits=4)
     # pages in reverse order of the dense blocks
     nb = 1024 // block_rows
     kp = k.view(B, Hkv, nb, block_rows, D).permute(0, 2, 1, 3, 4).reshape(B * nb, Hkv, block_rows, D).flip(0).contiguous()
     vp = v.view(B, Hkv, nb, block_rows, D).permute(0, 2, 1, 3, 4).reshape(B * nb, Hkv, block_rows, D).flip(0).contiguous()
     table = (B * nb - 1 - torch.arange(B * nb, dtype=torch.int32, device="cuda")).view(B, nb).contiguous()
-    paged = binding.sdpa_paged(q, kp, vp, lens_d, table, splits=4)
-    torch.cuda.synchronize()
-    assert torch.equal(dense, paged)
+    for Sq, causal, exact in ((200, True, True), (200, False, True), (1, False, False)):
+        q = make_qkv(B, H, Sq, D, "bf16", seed=95)[0].cuda()
+        dense = binding.sdpa_kv(q, k, v, kv_lens=lens_d, splits=4, causal=causal)
+        paged = binding.sdpa_paged(q, kp, vp, lens_d, table, splits=4, causal=causal)
+        torch.cuda.synchronize()
+        if exact:
+            assert torch.equal(dense, paged), f"Sq={Sq} causal={causal}"
+        else:
+            assert float((dense.float() - paged.float()).abs().max()) <= TOL["bf16"] / 4
