@@ -74,3 +74,9 @@ def test_main_loop_of_the_headline_kernels_touches_no_scratch_memory(src, tmp_pa
         n = scratch_ops_in_first_loop(lines)
         assert n == 0, f"{name}: {n} scratch accesses inside the main loop (T_N = {m.group(1)})"
     assert checked == 2, f"expected the 128x32 and 128x64 instantiations, found {checked}"
+    # every instantiation has two loops (unmasked tiles, masked tiles) and nothing else: a buffer descriptor
+    # the compiler takes for lane-dependent turns each of its loads into a loop over distinct descriptors
+    # (this happened to the paged-cache variant and cost a quarter of its speed on short runs)
+    for name, lines in kernels.items():
+        loops = sum("Loop Header" in line for line in lines)
+        assert loops <= 2, f"{name}: {loops} loops in the assembly (a load wrapped in a descriptor loop?)"
