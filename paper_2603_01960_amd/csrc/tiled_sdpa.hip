@@ -31,9 +31,12 @@ void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
     // or four (D = 64) wavefronts per SIMD; they are level with or ahead of 64-row tiles everywhere
     // (1-6 %) except under the causal mask at D = 64 and 128, where the finer diagonal does not pay for
     // the extra barriers.  At D = 160 only the 32-row tile leaves room for two workgroups per CU.
+    // At D = 128 the masked step of the 32-row tile (the diagonal band) does not fit its 168 registers
+    // and spills; on a short causal sequence most tiles are masked, and the 64-row tile is a quarter
+    // faster there (S = 197, 333).
     *tm = S <= 64 ? 64 : 128;
     *tn = 32;
-    if (causal && S >= 512 && (D == 64 || D == 128)) *tn = 64;
+    if (causal && ((S >= 512 && D == 64) || (S > 64 && D == 128))) *tn = 64;
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
