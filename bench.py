@@ -367,7 +367,7 @@ def bench_bwd(pkg, torch, args, flags):
         "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(tf / PEAK_MFMA_TFLOPS, 4),
                      # all four kernels of a call, FETCH_SIZE + WRITE_SIZE scaled (profiles/sdpa_bwd_C4_C2.md)
-                     "traffic": 2682.8e6 if (w.name == "C4" and dtype == "bf16" and not causal and Hkv == w.H) else None,
+                     "traffic": 2515.7e6 if (w.name == "C4" and dtype == "bf16" and not causal and Hkv == w.H) else None,
                      "kernel": ("sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dK+dV> + sdpa_bwd_kernel<dQ>" if w.D == 64 else
                                 "sdpa_bwd_prepare_kernel + sdpa_bwd_kernel<dV> + sdpa_bwd_kernel<dK> + sdpa_bwd_kernel<dQ>"),
                      "ms_avg_all_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
