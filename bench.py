@@ -27,10 +27,13 @@ PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
 # scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
 MEASURED_TRAFFIC_BYTES = {
-    ("C4", "bf16"): 698.9e6,   # 543.7 MB fetched + 155.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
-    ("C5", "f16"): 482.4e6,    # 404.8 MB + 77.6 MB          (profiles/sdpa_fwd_C5_f16.md)
-    ("C3", "bf16"): 77.6e6,    # 58.2 MB + 19.4 MB           (profiles/sdpa_fwd_C3_bf16.md)
-    ("C2", "f16"): 33.7e6,     # 25.3 MB + 8.4 MB            (profiles/sdpa_fwd_C2_f16.md)
+    # (workload, dtype, (T_M, T_N))
+    ("C4", "bf16", (128, 64)): 537.0e6,   # 402.8 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
+    ("C4", "bf16", (128, 32)): 697.5e6,   # 542.3 MB + 155.2 MB        (profiles/sdpa_fwd_C4_bf16_tile_128x32.md)
+    ("C4", "bf16", (64, 64)): 798.4e6,    # 664.2 MB + 134.2 MB        (profiles/sdpa_fwd_C4_bf16_tile_64x64.md)
+    ("C5", "f16", (128, 64)): 402.8e6,    # 335.7 MB + 67.1 MB         (profiles/sdpa_fwd_C5_f16.md)
+    ("C3", "bf16", (128, 32)): 77.6e6,    # 58.2 MB + 19.4 MB          (profiles/sdpa_fwd_C3_bf16.md)
+    ("C2", "f16", (128, 64)): 33.7e6,     # 25.3 MB + 8.4 MB           (profiles/sdpa_fwd_C2_f16.md)
 }
 
 # The paper's own figures, other hardware (NVIDIA DGX GB10): context only, never a target.
@@ -456,9 +459,9 @@ def main():
         gbs = comp_bytes / (r["kernel_ms_avg"] * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4)}
-    # the committed counters were taken with the 128 x 32 tile: they say nothing about another one
-    profiled = not args.causal and args.input_fill == "normal" and (tm, tn) == (128, 32)
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dtype)) if profiled else None
+    # counters are committed per tile: one tile's traffic says nothing about another's
+    profiled = not args.causal and args.input_fill == "normal" and not args.linear_grid
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dtype, (tm, tn))) if profiled else None
     roofline["kernel"] = f"sdpa_fwd_kernel<{dtype},D={w.D},T_M={tm},T_N={tn}>"
     roofline["kernel_ms_avg"] = round(r["kernel_ms_avg"], 5)
     roofline["kernel_ms_median"] = round(r["kernel_ms_median"], 5)

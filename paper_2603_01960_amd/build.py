@@ -25,6 +25,19 @@ FLAGS = [
     f"-I{INCLUDE}", f"-I{CSRC}",
 ]
 
+# The forward kernels on 64-row K/V tiles (up to D = 128) are scheduled by LLVM's iterative ILP
+# strategy: measured 3-5 % faster than the default on every one of them.  The same strategy halves the
+# speed of the 32-row tile kernels (it lengthens live ranges past their 168-register budget) and does
+# not get through the backward kernels, so it is applied per translation unit and never elsewhere.
+ILP_SCHED = ["-mllvm", "-amdgpu-sched-strategy=iterative-ilp"]
+
+
+def extra_flags(src: Path) -> list[str]:
+    name = src.name
+    if name.startswith("sdpa_fwd_") and name.endswith("_tn64.hip") and "_d160_" not in name:
+        return ILP_SCHED
+    return []
+
 
 def sources():
     return sorted(CSRC.glob("*.hip"))
@@ -32,7 +45,7 @@ def sources():
 
 def _compile(src: Path) -> Path:
     obj = OBJ / (src.stem + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", str(src), "-o", str(obj)]
+    cmd = [HIPCC, *FLAGS, *extra_flags(src), "-c", str(src), "-o", str(obj)]
     res = subprocess.run(cmd, capture_output=True, text=True)
     noise = ("packed-fp32-ops", "is not a recognized feature")
     err = "\n".join(l for l in res.stderr.splitlines() if not any(n in l for n in noise))

@@ -1,6 +1,10 @@
-// Forward-kernel instantiations: element type f16, head dim 160.
+// Forward-kernel instantiations: element type f16, head dim 160, K/V tiles of 32 rows.
 #include "sdpa_fwd_inst.h"
 
 namespace tsdpa {
-int launch_f16_d160(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<_Float16, 160>(tile_m, tile_n, a); }
+int launch_f16_d160_tn64(int tile_m, const LaunchArgs &a);
+int launch_f16_d160(int tile_m, int tile_n, const LaunchArgs &a)
+{
+    return launch_dispatch<_Float16, 160>(tile_m, tile_n, a, &launch_f16_d160_tn64);
+}
 }  // namespace tsdpa

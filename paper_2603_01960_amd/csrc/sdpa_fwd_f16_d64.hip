@@ -1,6 +1,10 @@
-// Forward-kernel instantiations: element type f16, head dim 64.
+// Forward-kernel instantiations: element type f16, head dim 64, K/V tiles of 32 and 128 rows.
 #include "sdpa_fwd_inst.h"
 
 namespace tsdpa {
-int launch_f16_d64(int tile_m, int tile_n, const LaunchArgs &a) { return launch_dispatch<_Float16, 64>(tile_m, tile_n, a); }
+int launch_f16_d64_tn64(int tile_m, const LaunchArgs &a);
+int launch_f16_d64(int tile_m, int tile_n, const LaunchArgs &a)
+{
+    return launch_dispatch<_Float16, 64>(tile_m, tile_n, a, &launch_f16_d64_tn64);
+}
 }  // namespace tsdpa

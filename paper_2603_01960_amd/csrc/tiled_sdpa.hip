@@ -27,16 +27,18 @@ void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
 {
     (void)BH;
     // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts) win at every
-    // configuration measured.  K/V tiles of 32 rows are the ones whose loop fits three (D = 96, 128)
-    // or four (D = 64) wavefronts per SIMD; they are level with or ahead of 64-row tiles everywhere
-    // (1-6 %) except under the causal mask at D = 64 and 128, where the finer diagonal does not pay for
-    // the extra barriers.  At D = 160 only the 32-row tile leaves room for two workgroups per CU.
-    // At D = 128 the masked step of the 32-row tile (the diagonal band) does not fit its 168 registers
-    // and spills; on a short causal sequence most tiles are masked, and the 64-row tile is a quarter
-    // faster there (S = 197, 333).
+    // configuration measured.  Up to D = 128 the two K/V tile heights are within 2 % of each other on
+    // long sequences: 32 rows fit three wavefronts per SIMD, 64 rows halve the barriers and are built
+    // with the scheduler that suits them.  The 64-row tile is ahead by 4-14 % on mid-length sequences
+    // (512-2048) and under the causal mask, where the finer diagonal of the 32-row tile does not pay
+    // for its barriers; at D = 128 its masked step also spills, so every S above one tile takes 64
+    // rows there.  Short sequences at D = 64 and 96 (S = 197, 333) are level or better on 32 rows.
+    // At D = 160 only the 32-row tile leaves room for two workgroups per CU.
     *tm = S <= 64 ? 64 : 128;
     *tn = 32;
-    if (causal && ((S >= 512 && D == 64) || (S > 64 && D == 128))) *tn = 64;
+    if (D == 128 && S > 64) *tn = 64;
+    if (D < 128 && S >= 512) *tn = 64;
+    (void)causal;
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
@@ -94,7 +96,7 @@ int validate_shape_kv(int B, int H, int Sq, int Skv, int D, int dtype, unsigned 
 void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 {
     *tm = Sq <= 64 ? 64 : 128;
-    *tn = (Skv >= 512 && D != 160 && D != 96) ? 64 : 32;   // decoding shapes are bound by the cache read, not by the loop
+    *tn = (Skv >= 512 && D != 160) ? 64 : 32;   // decoding shapes are bound by the cache read, not by the loop
 }
 
 }  // namespace
