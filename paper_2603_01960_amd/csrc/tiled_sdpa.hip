@@ -57,7 +57,7 @@ int validate_shape(int B, int H, int S, int D, int dtype)
 }
 
 // Splits along the key axis (from timings on MI355X).  None when the query tiles alone give every CU
-// two workgroups.  Otherwise aim for two workgroups per CU if every split then still streams 32 tiles
+// two workgroups.  Otherwise aim for two workgroups per CU if every split then still streams 16 tiles
 // or more (long caches: more loads in flight pay), else for one per CU, never cutting runs shorter
 // than 4 tiles for up to 64 query rows or 16 tiles beyond (each split of a query tile writes and the
 // merge re-reads T_M x D floats, which a short run does not amortise).
@@ -67,7 +67,7 @@ int pick_splits(int BH, int Sq, int Skv, int tm, int tn)
     const int64_t tiles = (Skv + tn - 1) / tn;
     if (base <= 0 || base >= 512) return 1;
     int64_t want = (512 + base - 1) / base;
-    if (tiles / want < 32) {
+    if (tiles / want < 16) {
         want = (256 + base - 1) / base;
         const int64_t shortest = Sq <= 64 ? 4 : 16;
         const int64_t most = tiles / shortest > 1 ? tiles / shortest : 1;
@@ -376,7 +376,20 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
         }
     }
     if (err != 0) return TSDPA_ERR_LAUNCH;
-    if (splits > 1) {
+    if (splits > 4) {
+        // many splits (decoding: few rows): one workgroup per row, the splits shared among eight threads
+        static_assert(tsdpa::kMergeLanes * tsdpa::kMergePerLane >= TSDPA_MAX_SPLITS, "every split needs a thread");
+        const size_t out_rows = (size_t)B * H * Sq;
+        if (out_rows > (size_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
+        const dim3 block(D / 4, tsdpa::kMergeLanes);
+        if (dtype == TSDPA_F16)
+            hipLaunchKernelGGL(tsdpa::sdpa_merge_wide_kernel<_Float16>, dim3((unsigned)out_rows), block, 0, (hipStream_t)stream,
+                               (const float *)workspace, (_Float16 *)o, lse, B * Hkv, rows, D, splits);
+        else
+            hipLaunchKernelGGL(tsdpa::sdpa_merge_wide_kernel<__bf16>, dim3((unsigned)out_rows), block, 0, (hipStream_t)stream,
+                               (const float *)workspace, (__bf16 *)o, lse, B * Hkv, rows, D, splits);
+        if (hipGetLastError() != hipSuccess) return TSDPA_ERR_LAUNCH;
+    } else if (splits > 1) {
         const size_t threads = (size_t)B * H * Sq * (D / 4);
         const unsigned blocks = (unsigned)((threads + 255) / 256);
         if (dtype == TSDPA_F16)

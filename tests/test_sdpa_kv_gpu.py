@@ -300,6 +300,19 @@ def check_kv_lens(B, H, Hkv, Sq, cap, D, dtype, lens, causal, splits, tile=None)
     say(f"        worst max|dO|={worst:.3e}")
 
 
+@pytest.mark.parametrize("D", [64, 96, 128, 160])
+@pytest.mark.parametrize("splits", [5, 8, 9, 31, 64, 128])
+def test_many_splits_take_the_one_row_per_workgroup_merge(D, splits):
+    """Above four splits the partial states of a row are combined by eight threads per column group
+    through the LDS: every head dim (its block is D/4 x 8 threads), split counts that do not divide by
+    eight, entries whose later splits (or all of them) see no key, grouped heads and LSE."""
+    dtype = "bf16" if D in (64, 160) else "f16"
+    check_kv_lens(4, 4, 2, 1, 1100, D, dtype, [1100, 0, 65, 513], False, splits)
+    check_kv_lens(2, 4, 1, 3, 900, D, dtype, [900, 2], True, splits)
+    q, k, v = make_q_kv(1, 2, 70, 2100, D, dtype, seed=9300 + D + splits)     # two query tiles of 64 rows
+    check_kv(q, k, v, dtype, splits=splits, causal=True, tile=(64, 64), tag="wide merge, chunk")
+
+
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 @pytest.mark.parametrize("causal", [False, True])
 @pytest.mark.parametrize("splits", [0, 1, 4])
