@@ -12,7 +12,8 @@
 // then (m, l) pairs as float [BH][splits][S][2].
 //
 // Two kernels.  sdpa_merge_kernel: one thread produces 4 consecutive output columns and walks the
-// splits itself; right for the few splits of a long prefill chunk, where rows are many.
+// splits itself, eight loads in flight at a time; right for up to eight splits, and for any split count
+// when the rows are many (a long prefill chunk), where the other threads hide the waiting.
 // sdpa_merge_wide_kernel: one workgroup per output row, kMergeLanes threads per column group that
 // take every kMergeLanes-th split each and combine through the LDS; for the many splits of a decoding
 // step, where rows are few and a walk over 32 splits would be a chain of load latencies longer than

@@ -376,11 +376,14 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
         }
     }
     if (err != 0) return TSDPA_ERR_LAUNCH;
-    if (splits > 4) {
-        // many splits (decoding: few rows): one workgroup per row, the splits shared among eight threads
+    const size_t out_rows = (size_t)B * H * Sq;
+    // Which merge: with more than eight splits a thread that walks them waits for its loads in several
+    // batches, and when the rows are few (decoding) nothing else hides that: one workgroup per row, the
+    // splits shared among eight threads (32 splits of 32 rows: 3.5 us against 12.5 us).  With thousands of
+    // rows the walking threads are many enough to hide it themselves and launch an eighth of the threads
+    // (8 splits of 8192 rows: 47 us per call against 55 us).
+    if (splits > 8 && out_rows <= 2048) {
         static_assert(tsdpa::kMergeLanes * tsdpa::kMergePerLane >= TSDPA_MAX_SPLITS, "every split needs a thread");
-        const size_t out_rows = (size_t)B * H * Sq;
-        if (out_rows > (size_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
         const dim3 block(D / 4, tsdpa::kMergeLanes);
         if (dtype == TSDPA_F16)
             hipLaunchKernelGGL(tsdpa::sdpa_merge_wide_kernel<_Float16>, dim3((unsigned)out_rows), block, 0, (hipStream_t)stream,
@@ -390,7 +393,7 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
                                (const float *)workspace, (__bf16 *)o, lse, B * Hkv, rows, D, splits);
         if (hipGetLastError() != hipSuccess) return TSDPA_ERR_LAUNCH;
     } else if (splits > 1) {
-        const size_t threads = (size_t)B * H * Sq * (D / 4);
+        const size_t threads = out_rows * (D / 4);
         const unsigned blocks = (unsigned)((threads + 255) / 256);
         if (dtype == TSDPA_F16)
             hipLaunchKernelGGL(tsdpa::sdpa_merge_kernel<_Float16>, dim3(blocks), dim3(256), 0, (hipStream_t)stream,

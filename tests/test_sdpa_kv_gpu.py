@@ -303,8 +303,8 @@ def check_kv_lens(B, H, Hkv, Sq, cap, D, dtype, lens, causal, splits, tile=None)
 @pytest.mark.parametrize("D", [64, 96, 128, 160])
 @pytest.mark.parametrize("splits", [5, 8, 9, 31, 64, 128])
 def test_many_splits_take_the_one_row_per_workgroup_merge(D, splits):
-    """Above four splits the partial states of a row are combined by eight threads per column group
-    through the LDS: every head dim (its block is D/4 x 8 threads), split counts that do not divide by
+    """Above eight splits (and up to 2048 output rows) the partial states of a row are combined by eight
+    threads per column group through the LDS, otherwise by one thread that walks them: every head dim (its block is D/4 x 8 threads), split counts that do not divide by
     eight, entries whose later splits (or all of them) see no key, grouped heads and LSE."""
     dtype = "bf16" if D in (64, 160) else "f16"
     check_kv_lens(4, 4, 2, 1, 1100, D, dtype, [1100, 0, 65, 513], False, splits)
