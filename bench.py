@@ -210,6 +210,24 @@ def hbm_copy_ceiling(torch, mib=1024, steps=10):
     return round(2 * n / (a.elapsed_time(b) / steps) / 1e6, 1)
 
 
+def hbm_read_ceiling(pkg, torch, mib=2048, steps=10):
+    """GB/s of a read-only stream over a buffer too large for any cache (tiled_sdpa_probe_hbm_read): what
+    reading a K/V cache once can be compared with on this GPU right now, next to the published 8 TB/s."""
+    src = torch.empty(mib * (1 << 20), dtype=torch.uint8, device="cuda").fill_(5)
+    sink = torch.empty(512 * 256, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(2):
+        done = pkg.probe_hbm_read(src.data_ptr(), src.numel(), sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(steps):
+        pkg.probe_hbm_read(src.data_ptr(), src.numel(), sink.data_ptr(), stream)
+    b.record()
+    torch.cuda.synchronize()
+    return round(done / (a.elapsed_time(b) / steps) / 1e6, 1)
+
+
 def mfma_ceilings(pkg, torch, dtype, iters=4000):
     """What a register-resident MFMA stream sustains on this GPU right now (TFLOP/s), with random and
     with constant operand data; the gap is the clock the chip gives up to its power limit."""
@@ -309,6 +327,9 @@ def bench_kv(pkg, torch, args, tile, flags):
         gbs = comp_bytes / (ms * 1e-3) / 1e9
         roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    if roofline["bound"] == "hbm" and not args.no_ceilings:
+        roofline["hbm_read_ceiling_GBs"] = hbm_read_ceiling(pkg, torch)
+        roofline["frac_of_hbm_read_ceiling"] = round(roofline["achieved"] / roofline["hbm_read_ceiling_GBs"], 4)
     roofline.update({"traffic": None, "kernel": "sdpa_fwd_kernel<KV> + sdpa_merge_kernel" if splits > 1 else "sdpa_fwd_kernel<KV>",
                      "ms_avg_both_kernels": round(ms, 5), "algorithmic_flops_per_launch": flops,
                      "compulsory_hbm_bytes_per_launch": comp_bytes})

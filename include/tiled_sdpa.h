@@ -289,6 +289,19 @@ unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S);
 int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink, double *flops,
                           void *stream);
 
+/*
+ * Measurement aid, not part of the attention path: enqueue a kernel that reads `bytes` of device memory at
+ * `src` once (8192 workgroups, each a contiguous run, four 16-byte loads per lane in flight) and writes
+ * nothing but one word per workgroup into `sink` (device, at least 512*256 floats).  What a decoding step
+ * (Section 8: reading the K/V cache once is all it does) can be compared with besides the published
+ * HBM figure: the rate a pure read stream sustains on this GPU.  src: device, 16-byte aligned; bytes: at
+ * least 128 MiB (smaller is refused as a bad shape), the part that does not fill a whole loop trip of every
+ * workgroup is not read; bytes_read (host pointer, may be NULL) receives the bytes the launch does read.
+ * Returns a status code.
+ */
+int tiled_sdpa_probe_hbm_read(const void *src, unsigned long long bytes, float *sink, double *bytes_read,
+                              void *stream);
+
 /* Human-readable text for a status code (static storage, never NULL). */
 const char *tiled_sdpa_status_string(int status);
 

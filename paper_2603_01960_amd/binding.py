@@ -34,6 +34,7 @@ EXPORTS = (
     "tiled_sdpa_kv_default_splits",
     "tiled_sdpa_kv_workspace_bytes",
     "tiled_sdpa_probe_mfma",
+    "tiled_sdpa_probe_hbm_read",
     "tiled_sdpa_status_string",
     "tiled_sdpa_version",
 )
@@ -88,6 +89,8 @@ def load_library():
     lib.tiled_sdpa_bwd_gqa.argtypes = [vp] * 9 + [ci, ci, ci, ci, ci, cf, ci, ctypes.c_uint, vp, ctypes.c_ulonglong, vp]
     lib.tiled_sdpa_bwd_workspace_bytes.restype = ctypes.c_ulonglong
     lib.tiled_sdpa_bwd_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.tiled_sdpa_probe_hbm_read.restype = ci
+    lib.tiled_sdpa_probe_hbm_read.argtypes = [vp, ctypes.c_ulonglong, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tiled_sdpa_probe_mfma.restype = ci
     lib.tiled_sdpa_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.tiled_sdpa_status_string.restype = ctypes.c_char_p
@@ -170,6 +173,16 @@ def probe_mfma(dtype: int, random_operands, iters: int, sink=None, stream=None) 
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return flops.value
+
+
+def probe_hbm_read(src_ptr: int, nbytes: int, sink_ptr: int, stream=None) -> float:
+    """Enqueue the read-only stream over ``nbytes`` at ``src_ptr`` (see tiled_sdpa_probe_hbm_read); returns
+    the bytes it reads."""
+    done = ctypes.c_double(0.0)
+    st = load_library().tiled_sdpa_probe_hbm_read(src_ptr, nbytes, sink_ptr, ctypes.byref(done), stream)
+    if st != 0:
+        raise TiledSdpaError(st, status_string(st))
+    return done.value
 
 
 def tiled_sdpa_fwd(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, B, H, S, D, scale, dtype, stream) -> int:

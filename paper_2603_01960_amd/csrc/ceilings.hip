@@ -137,6 +137,28 @@ __global__ void __launch_bounds__(256) mfma_mix_stream(float *sink, int iters)
 #endif
 }
 
+// Read-only stream: every workgroup walks a contiguous run of 16-byte words, four loads per lane in
+// flight, and keeps an XOR of what it read so that the loads cannot be dropped.
+constexpr int kReadGrid = 8192;
+constexpr int kReadStep = 1024;               // 16-byte words a workgroup reads per loop trip (256 lanes x 4)
+
+__global__ void __launch_bounds__(256)
+hbm_read_stream(const uint4 *__restrict__ src, float *__restrict__ sink, int words_per_group)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint4 *p = src + (size_t)blockIdx.x * words_per_group;
+    uint4 acc = {0u, 0u, 0u, 0u};
+    for (int i = threadIdx.x; i < words_per_group; i += kReadStep) {      // words_per_group is a multiple of kReadStep
+        const uint4 a = p[i], b = p[i + 256], c = p[i + 512], d = p[i + 768];
+        acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
+        acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+        acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
+        acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+    }
+    if (threadIdx.x == 0) sink[blockIdx.x % (512 * 256)] = (float)((acc.x ^ acc.y ^ acc.z ^ acc.w) & 0xFFFFu);
+#endif
+}
+
 }  // namespace
 
 extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink,
@@ -156,5 +178,19 @@ extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, 
         hipLaunchKernelGGL(mfma_stream<true>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
     else
         hipLaunchKernelGGL(mfma_stream<false>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters, random_operands);
+    return hipGetLastError() == hipSuccess ? TSDPA_OK : TSDPA_ERR_LAUNCH;
+}
+
+extern "C" int tiled_sdpa_probe_hbm_read(const void *src, unsigned long long bytes, float *sink,
+                                         double *bytes_read, void *stream)
+{
+    if (!src || !sink) return TSDPA_ERR_NULL_PTR;
+    if (((uintptr_t)src & 15u) != 0) return TSDPA_ERR_MISALIGNED;
+    // whole loop trips only, so that no access needs a bounds check: the tail that does not fill one is not read
+    const unsigned long long per_group = bytes / 16 / kReadGrid / kReadStep * kReadStep;
+    if (per_group == 0 || per_group > 0x7FFFFFFFull) return TSDPA_ERR_BAD_SHAPE;
+    if (bytes_read) *bytes_read = (double)per_group * 16.0 * kReadGrid;
+    hipLaunchKernelGGL(hbm_read_stream, dim3(kReadGrid), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)src, sink, (int)per_group);
     return hipGetLastError() == hipSuccess ? TSDPA_OK : TSDPA_ERR_LAUNCH;
 }

@@ -276,6 +276,12 @@ def test_probe_validates_before_touching_the_gpu(lib):
     assert lib.tiled_sdpa_probe_mfma(1, 1, 0, P, ctypes.byref(fl), None) == OK     # iters = 0: flops only
     assert fl.value == 0.0
     assert binding.probe_mfma(binding.BF16, True, 0) == 0.0
+    # the read stream: null pointers, alignment, and a buffer too small to give every workgroup a loop trip
+    assert lib.tiled_sdpa_probe_hbm_read(None, 1 << 30, P, ctypes.byref(fl), None) == NULL
+    assert lib.tiled_sdpa_probe_hbm_read(P, 1 << 30, None, ctypes.byref(fl), None) == NULL
+    assert lib.tiled_sdpa_probe_hbm_read(P + 8, 1 << 30, P, ctypes.byref(fl), None) == ALIGN
+    assert lib.tiled_sdpa_probe_hbm_read(P, (128 << 20) - 1, P, ctypes.byref(fl), None) == SHAPE
+    assert lib.tiled_sdpa_probe_hbm_read(P, 0, P, ctypes.byref(fl), None) == SHAPE
 
 
 def test_default_tile_is_a_legal_tile(lib):

@@ -257,6 +257,27 @@ def test_mfma_probe_runs_and_reports_its_flops():
     assert float(sink[0]) == 64 * 16 * 16      # 64 MFMAs x 16 accumulator elements summed x 16
 
 
+def test_read_stream_probe_reads_what_it_reports_and_checks_every_word():
+    """Every lane keeps an XOR of the words it read and the first lane of a workgroup leaves its own in the
+    sink: zeros give zero, and a byte changed in a word that lane reads changes that workgroup's entry only."""
+    nbytes = (128 << 20) + 4096 + 16                  # one loop trip per workgroup, plus a tail that is not read
+    src = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.full((512 * 256,), -1.0, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    done = binding.probe_hbm_read(src.data_ptr(), nbytes, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    assert done == 128 << 20
+    assert torch.all(sink[:8192] == 0) and torch.all(sink[8192:] == -1)
+    per_group = (128 << 20) // 8192
+    assert per_group == 1024 * 16                      # one loop trip: 256 lanes x 4 loads of 16 bytes
+    src[5 * per_group + 512 * 16 + 1] = 7              # workgroup 5, third load of lane 0
+    src[(128 << 20) + 100] = 9                         # in the tail: must not be read
+    binding.probe_hbm_read(src.data_ptr(), nbytes, sink.data_ptr(), stream)
+    torch.cuda.synchronize()
+    changed = torch.nonzero(sink[:8192]).flatten().tolist()
+    assert changed == [5], changed
+
+
 # ------------------------------------------------------------------ head dims 96 and 160 (Section 4.3 grid)
 @pytest.mark.parametrize("tile", TILES)
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
