@@ -516,6 +516,9 @@ def main():
         out["frac_of_mfma_only_ceiling_random_operands"] = round(kern_tflops / ceil["random_operands"], 4)
         out["frac_of_loop_mix_ceiling"] = round(kern_tflops / ceil["random_operands_plus_loop_mix"], 4)
         out["hbm_copy_ceiling_GBs"] = hbm_copy_ceiling(torch)
+        if roofline["bound"] == "hbm":
+            out["hbm_read_ceiling_GBs"] = hbm_read_ceiling(pkg, torch)
+            out["frac_of_hbm_read_ceiling"] = round(roofline["achieved"] / out["hbm_read_ceiling_GBs"], 4)
 
     if args.sweep_tiles:
         sweep = {}
