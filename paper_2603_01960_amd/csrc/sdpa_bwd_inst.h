@@ -20,8 +20,9 @@ template <> struct BwdShape<96>  { static constexpr int NW = 4, WPS[4] = {2, 2, 
 template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[4] = {2, 2, 2, 2}, TS[4] = {32, 32, 64, 32}; static constexpr bool FUSED_DKV = false; };
 // D = 160 (512-byte LDS rows): at two wavefronts per SIMD the dK and dQ passes spill 55-65 registers; with the
 // whole register file of a SIMD for one wavefront (the compiler then places accumulators in AGPRs) nothing
-// spills and the pass is 38 % faster although only one workgroup fits a CU
-template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[4] = {1, 1, 1, 1}, TS[4] = {64, 32, 64, 32}; static constexpr bool FUSED_DKV = false; };
+// spills and the pass is 38 % faster although only one workgroup fits a CU.  The dV pass (one product fewer,
+// no dP) does fit 256 registers on 32-row tiles, whose 64 KB of LDS admit a second workgroup: +12 % per call.
+template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[4] = {1, 1, 2, 1}, TS[4] = {64, 32, 32, 32}; static constexpr bool FUSED_DKV = false; };
 
 template <typename T, int D, int MODE, bool GRP>
 int launch_bwd_pass(const BwdLaunchArgs &a)
