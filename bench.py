@@ -24,17 +24,31 @@ sys.path.insert(0, ROOT)
 PEAK_MFMA_TFLOPS = 2500.0      # MI355X dense FP16/BF16 MFMA, published
 PEAK_HBM_GBS = 8000.0          # MI355X HBM3E, published
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same command,
-# scaled by the copy-kernel calibration (see profiles/); None where no such run is committed.
-MEASURED_TRAFFIC_BYTES = {
-    # (workload, dtype, (T_M, T_N))
-    ("C4", "bf16", (128, 64)): 537.0e6,   # 402.8 MB fetched + 134.2 MB written (profiles/sdpa_fwd_C4_bf16.md)
-    ("C4", "bf16", (128, 32)): 697.5e6,   # 542.3 MB + 155.2 MB        (profiles/sdpa_fwd_C4_bf16_tile_128x32.md)
-    ("C4", "bf16", (64, 64)): 798.4e6,    # 664.2 MB + 134.2 MB        (profiles/sdpa_fwd_C4_bf16_tile_64x64.md)
-    ("C5", "f16", (128, 64)): 402.8e6,    # 335.7 MB + 67.1 MB         (profiles/sdpa_fwd_C5_f16.md)
-    ("C3", "bf16", (128, 32)): 77.6e6,    # 58.2 MB + 19.4 MB          (profiles/sdpa_fwd_C3_bf16.md)
-    ("C2", "f16", (128, 64)): 33.7e6,     # 25.3 MB + 8.4 MB           (profiles/sdpa_fwd_C2_f16.md)
-}
+PROFILES = os.path.join(ROOT, "profiles")
+
+
+def profiled_traffic(workload, dtype, D, tm, tn):
+    """HBM bytes per launch of a workload's kernel as the committed rocprofv3 summary states them
+    (FETCH_SIZE + WRITE_SIZE per dispatch, scaled by the copy-kernel calibration): the "total" row of
+    profiles/sdpa_fwd_<workload>_<dtype>[_tile_<T_M>x<T_N>].md whose `Kernel:` line names this very
+    instantiation.  Returns (bytes or None, source file or the reason there is none)."""
+    import re
+    nw = tm // 32
+    want = re.compile(r"sdpa_fwd_kernelI(DF16_|DF16b)Li%dELi%dELi%dELi\dELi0E" % (D, nw, tn))
+    elem = "DF16_" if dtype == "f16" else "DF16b"
+    for name in (f"sdpa_fwd_{workload}_{dtype}_tile_{tm}x{tn}.md", f"sdpa_fwd_{workload}_{dtype}.md"):
+        path = os.path.join(PROFILES, name)
+        if not os.path.exists(path):
+            continue
+        text = open(path).read()
+        m = want.search(text)
+        if m is None or m.group(1) != elem:
+            continue
+        t = re.search(r"^\|\s*total\s*\|[^|]*\|\s*([0-9.]+)\s*MB\s*\|", text, re.M)
+        if t:
+            return float(t.group(1)) * 1e6, "profiles/" + name
+    return None, f"no committed counter run of sdpa_fwd_kernel<{dtype},D={D},T_M={tm},T_N={tn}> on {workload}"
+
 
 # The paper's own figures, other hardware (NVIDIA DGX GB10): context only, never a target.
 PAPER_CONTEXT = {
@@ -74,12 +88,17 @@ def parse_args():
                     help="causal mask (Section 4.1.3); flops are then counted as half of the non-causal figure")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the baseline sample")
-    ap.add_argument("--all-workloads", action="store_true", help="also time the other configurations")
+    ap.add_argument("--no-all-workloads", dest="all_workloads", action="store_false",
+                    help="skip the per-configuration summary (C1..C5: back-to-back, HIP-graph and cache-cold launch "
+                         "times, each against its own roofline, and the error against the CPU oracle)")
+    ap.add_argument("--csv", default=None,
+                    help="also write the tile sweep and the per-configuration summary as CSV rows with status and "
+                         "status_detail columns (unsupported cells are recorded, not dropped: Section 5 of the paper)")
     ap.add_argument("--no-tune", dest="tune", action="store_false",
                     help="take the library's heuristic tile; by default the tile is picked with tiled_sdpa_tune_tile "
-                         "(the paper's per-shape schedule search, Sections 4.2.2-4.2.3) before and outside the timed region")
-    ap.add_argument("--sweep-tiles", action="store_true",
-                    help="also time every legal (T_M, T_N) of the workload (the schedule knobs of the paper's Table 1)")
+                         "(the paper's per-shape schedule search, Table 1 and Sections 5.5-5.6) before and outside the timed region")
+    ap.add_argument("--no-sweep-tiles", dest="sweep_tiles", action="store_false",
+                    help="skip the sweep over every (T_M, T_N) of the workload (the schedule knobs of the paper's Table 1)")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the MFMA-only ceiling measurement")
     ap.add_argument("--input-fill", default="normal", choices=["normal", "zeros", "ones"],
                     help="normal = the seeded workload; zeros / ones = same shapes with constant data "
@@ -90,23 +109,34 @@ def parse_args():
     return ap.parse_args()
 
 
-def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal", shape=None, qk_std=None):
+_DEVICE_TENSORS = {}
+
+
+def device_workload(torch, name, dtype=None, fill="normal", shape=None, qk_std=None):
+    """(workload, dtype, q, k, v) with the seeded tensors on the GPU; one copy per configuration is kept
+    for the whole run (every leg of the bench then times and checks the same tensors)."""
     import dataclasses
-    from paper_2603_01960_amd.workloads import WORKLOADS, Workload, make_qkv, make_workload
-    if shape is not None:
-        B, H, S, D = shape
-        dtype = dtype or "bf16"
-        w = Workload(f"custom", B, H, S, D, (dtype,), 4242)
-        q, k, v = make_qkv(B, H, S, D, dtype, w.seed)
-    elif qk_std is not None:
-        w = dataclasses.replace(WORKLOADS[name], qk_std=float(qk_std))
-        q, k, v = make_qkv(w.B, w.H, w.S, w.D, dtype or w.dtypes[0], w.seed, w.qk_std, w.v_std)
-    else:
-        w, q, k, v = make_workload(name, dtype)
-    dtype = dtype or w.dtypes[0]
-    if fill != "normal":
-        q, k, v = (torch.zeros_like(t) if fill == "zeros" else torch.ones_like(t) for t in (q, k, v))
-    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    from paper_2603_01960_amd.workloads import WORKLOADS, Workload, make_qkv
+    key = (name, dtype, fill, shape, qk_std)
+    if key not in _DEVICE_TENSORS:
+        if shape is not None:
+            B, H, S, D = shape
+            dt = dtype or "bf16"
+            w = Workload("custom", B, H, S, D, (dt,), 4242)
+        else:
+            w = WORKLOADS[name]
+            if qk_std is not None:
+                w = dataclasses.replace(w, qk_std=float(qk_std))
+            dt = dtype or w.dtypes[0]
+        q, k, v = make_qkv(w.B, w.H, w.S, w.D, dt, w.seed, w.qk_std, w.v_std)
+        if fill != "normal":
+            q, k, v = (torch.zeros_like(t) if fill == "zeros" else torch.ones_like(t) for t in (q, k, v))
+        _DEVICE_TENSORS[key] = (w, dt, q.cuda(), k.cuda(), v.cuda())
+    return _DEVICE_TENSORS[key]
+
+
+def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fill="normal", shape=None, qk_std=None):
+    w, dtype, qd, kd, vd = device_workload(torch, name, dtype, fill, shape, qk_std)
     o = torch.empty_like(qd)
     run = lambda: pkg.sdpa(qd, kd, vd, out=o, tile=tile, flags=flags)
     for _ in range(warmup):
@@ -133,7 +163,7 @@ def time_workload(pkg, torch, name, dtype, steps, warmup, tile=None, flags=0, fi
         "kernel_ms_avg": region_ms / steps,
         "kernel_ms_median": statistics.median(per_launch_ms),
         "kernel_ms_p95": per_launch_ms[min(steps - 1, int(0.95 * steps))],
-        "tensors": (q, k, v),
+        "tensors": (qd, kd, vd), "o": o,
     }
 
 
@@ -143,11 +173,10 @@ def time_batched(pkg, torch, name, dtype, n, warmup, rotate=1):
     rotate > 1 cycles the launches over that many copies of (Q, K, V, O) in distinct memory, so that a
     launch finds none of its tensors in the L2 or in the 256 MB memory-side cache (a cache-cold figure
     for the workloads whose tensors would otherwise stay resident between launches)."""
-    from paper_2603_01960_amd.workloads import make_workload
-    w, q, k, v = make_workload(name, dtype)
-    sets = []
-    for _ in range(rotate):
-        qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    w, _, q, k, v = device_workload(torch, name, dtype)
+    sets = [(q, k, v, torch.empty_like(q))]
+    for _ in range(rotate - 1):
+        qd, kd, vd = q.clone(), k.clone(), v.clone()
         sets.append((qd, kd, vd, torch.empty_like(qd)))
     for i in range(max(warmup, rotate)):
         qd, kd, vd, o = sets[i % rotate]
@@ -160,15 +189,13 @@ def time_batched(pkg, torch, name, dtype, n, warmup, rotate=1):
         pkg.sdpa(qd, kd, vd, out=o)
     b.record()
     torch.cuda.synchronize()
-    return w, a.elapsed_time(b) / n
+    return w, a.elapsed_time(b) / n, sets[0][3]
 
 
 def time_graph_replay(pkg, torch, name, dtype, per_graph=20, replays=20):
     """Per-launch time of `per_graph` launches recorded once into a HIP graph and replayed: the rate of
     the kernel itself where the eager loop is bound by host time per call (C1)."""
-    from paper_2603_01960_amd.workloads import make_workload
-    w, q, k, v = make_workload(name, dtype)
-    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    w, _, qd, kd, vd = device_workload(torch, name, dtype)
     o = torch.empty_like(qd)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -399,27 +426,161 @@ def bench_bwd(pkg, torch, args, flags):
                      "executed_mfma_flops_per_launch": flops * (7.0 if w.D == 64 else 8.0) / 5.0}}), flush=True)
 
 
-def cpu_baseline(w, q, k, v, target_seconds):
-    """Time the unmodified float64 CPU checker on a bounded sample of the same workload."""
+TOL = {"f16": 2e-3, "bf16": 1.6e-2}     # max-abs error against the float64 oracle (the task's stated tolerances)
+
+
+def oracle_rows(w, q, k, v, rows):
+    """(seconds, float64 reference [B, H, len(rows), D]) of the unmodified CPU oracle on the given query
+    rows of every head (rows = None: the whole configuration)."""
     from oracle import sdpa_oracle
-    qn, kn, vn = (x.float().numpy() for x in (q, k, v))
+    qn, kn, vn = (x.float().cpu().numpy() for x in (q, k, v))
+    t = time.perf_counter()
+    ref = sdpa_oracle.sdpa(qn, kn, vn, rows=rows)
+    return time.perf_counter() - t, ref
+
+
+def max_abs_err(torch, o, ref, rows):
+    """max |float64(o) - ref| over the compared rows; o is the device output of a timed launch."""
+    import numpy as np
+    got = o if rows is None else o[:, :, torch.tensor(rows, device=o.device)]
+    return float(np.abs(got.double().cpu().numpy() - ref).max())
+
+
+def cpu_baseline(torch, w, dtype, q, k, v, o, target_seconds, causal=False):
+    """Time the unmodified float64 CPU oracle on a bounded sample of the same workload, and hold the
+    output of the timed launches against what it computed (the harness's correctness check, Section 4.2.3)."""
+    from oracle import sdpa_oracle
+    qn, kn, vn = (x.float().cpu().numpy() for x in (q, k, v))
     # calibrate on a few rows, then size the sample for ~target_seconds
     probe = list(range(0, w.S, max(1, w.S // 8)))[:8]
     t = time.perf_counter()
-    sdpa_oracle.sdpa(qn, kn, vn, rows=probe)
+    sdpa_oracle.sdpa(qn, kn, vn, rows=probe, causal=causal)
     dt = max(time.perf_counter() - t, 1e-4)
     nrows = int(min(w.S, max(len(probe), len(probe) * target_seconds / dt)))
     rows = sorted({(i * w.S) // nrows for i in range(nrows)})      # evenly spread over the sequence
     t = time.perf_counter()
-    sdpa_oracle.sdpa(qn, kn, vn, rows=rows)
+    ref = sdpa_oracle.sdpa(qn, kn, vn, rows=rows, causal=causal)
     dt = time.perf_counter() - t
-    flops = 4.0 * w.BH * len(rows) * w.S * w.D
-    return {
+    flops = 4.0 * w.BH * w.D * (sum(r + 1 for r in rows) if causal else len(rows) * w.S)
+    base = {
         "value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": sdpa_oracle.num_threads(),
         "kind": "oracle", "seconds": round(dt, 3),
         "sample": f"{w.name}: all {w.BH} heads x {len(rows)} of {w.S} query rows (evenly spaced) "
-                  f"against all {w.S} keys, float64",
+                  f"against {'the keys up to its own position' if causal else f'all {w.S} keys'}, float64",
     }
+    check = {"max_abs_err": max_abs_err(torch, o, ref, rows), "tol": TOL[dtype],
+             "rows_checked": len(rows) * w.BH, "rows_per_head": len(rows), "heads": w.BH,
+             "against": "the cpu_baseline sample (float64 oracle), output of the last timed launch"}
+    return base, check
+
+
+def roofline_of(w, ms, flops=None):
+    """The roof that bounds a configuration (arithmetic intensity on compulsory bytes against the ridge
+    point) and the fraction of it a launch of `ms` milliseconds reaches.  C1 (two or four workgroups)
+    is bound by the launch itself: no fraction is meaningful there."""
+    flops = w.flops if flops is None else flops
+    comp = w.compulsory_bytes(2)
+    if w.BH * ((w.S + 127) // 128) < 64:
+        return {"bound": "latency", "achieved": round(ms * 1e3, 3), "unit": "us per launch", "peak": None, "frac": None}
+    if flops / comp >= PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        tf = flops / (ms * 1e-3) / 1e12
+        return {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": round(tf / PEAK_MFMA_TFLOPS, 4)}
+    gbs = comp / (ms * 1e-3) / 1e9
+    return {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+            "frac": round(gbs / PEAK_HBM_GBS, 4)}
+
+
+def summarise_workloads(pkg, torch, args, headline_check):
+    """Every configuration of the metric (C1..C5) in the heuristic schedule: launch time back to back,
+    replayed from a HIP graph (short kernels), cache-cold (tensors in rotation), each against the roof
+    that bounds it; the CPU oracle's wall time on the whole of C1..C3; the error of a launch's output
+    against the oracle (whole configuration for C1..C3, every query-tile boundary row for C5; C4's is
+    the headline's check)."""
+    from paper_2603_01960_amd.workloads import sample_rows
+    out = {}
+    for name, dts in (("C1", ["f16"]), ("C2", ["f16", "bf16"]), ("C3", ["bf16"]), ("C4", ["bf16"]), ("C5", ["f16"])):
+        for dt in dts:
+            ww, ms, o = time_batched(pkg, torch, name, dt, max(20, args.steps), args.warmup)
+            code = pkg.F16 if dt == "f16" else pkg.BF16
+            tm, tn = pkg.binding.default_tile(ww.B, ww.H, ww.S, ww.D, code, 0)
+            e = {"shape": f"B={ww.B} H={ww.H} S={ww.S} D={ww.D} {dt}", "tile": [tm, tn],
+                 "ms_per_launch_back_to_back": round(ms, 5),
+                 "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
+                 "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1),
+                 "roofline": roofline_of(ww, ms), "status": "ok", "status_detail": ""}
+            if ms < 0.1:
+                gms = time_graph_replay(pkg, torch, name, dt)
+                e["hip_graph_replay"] = {
+                    "ms_per_launch": round(gms, 5), "tflops": round(ww.flops / (gms * 1e-3) / 1e12, 2),
+                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (gms * 1e-3) / 1e9, 1),
+                    "roofline": roofline_of(ww, gms)}
+            sets = -(-(1 << 30) // int(ww.compulsory_bytes(2)))      # >= 1 GiB of distinct tensors in rotation
+            if 1 < sets <= 64:
+                _, cms, _ = time_batched(pkg, torch, name, dt, max(4 * sets, args.steps), args.warmup, rotate=sets)
+                e["cache_cold"] = {
+                    "buffer_sets_in_rotation": sets, "ms_per_launch": round(cms, 5),
+                    "tflops": round(ww.flops / (cms * 1e-3) / 1e12, 2),
+                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (cms * 1e-3) / 1e9, 1),
+                    "roofline": roofline_of(ww, cms)}
+            if not args.no_cpu_baseline:
+                _, _, q, k, v = device_workload(torch, name, dt)
+                if name == "C4":
+                    e["check"] = headline_check      # the same tensors, checked on the headline's sample
+                else:
+                    rows = None if name in ("C1", "C2", "C3") else sample_rows(ww.S)
+                    secs, ref = oracle_rows(ww, q, k, v, rows)
+                    n = ww.S if rows is None else len(rows)
+                    e["check"] = {"max_abs_err": max_abs_err(torch, o, ref, rows), "tol": TOL[dt],
+                                  "rows_checked": n * ww.BH, "rows_per_head": n, "heads": ww.BH}
+                    if rows is None:
+                        e["cpu_oracle_seconds_whole_configuration"] = round(secs, 4)
+                if e.get("check") and not (e["check"]["max_abs_err"] <= e["check"]["tol"]):
+                    e["status"], e["status_detail"] = "error", "output outside the tolerance"
+            out[f"{name}_{dt}"] = e
+    return out
+
+
+def sweep_tiles(pkg, torch, args, w, flops, flags, shape):
+    """Every (T_M, T_N) of the paper's Table 1 grid {64,128} x {32,64,128} on the headline workload.  A
+    cell the library does not offer is recorded with its status, not dropped (Section 5)."""
+    sweep = {}
+    code = pkg.F16 if (args.dtype or w.dtypes[0]) == "f16" else pkg.BF16
+    for tm_ in (64, 128):
+        for tn_ in (32, 64, 128):
+            key = f"{tm_}x{tn_}"
+            try:
+                rr = time_workload(pkg, torch, args.workload, args.dtype, max(10, args.steps // 2), 3, (tm_, tn_), flags,
+                                   args.input_fill, shape, args.qk_std)
+            except pkg.binding.TiledSdpaError as exc:
+                sweep[key] = {"status": "unsupported", "status_detail": str(exc), "kernel_ms_avg": None,
+                              "tflops": None, "frac_of_mfma_peak": None}
+                continue
+            tf = flops / (rr["kernel_ms_avg"] * 1e-3) / 1e12
+            sweep[key] = {"status": "ok", "status_detail": "", "kernel_ms_avg": round(rr["kernel_ms_avg"], 5),
+                          "tflops": round(tf, 2), "frac_of_mfma_peak": round(tf / PEAK_MFMA_TFLOPS, 4)}
+    return sweep
+
+
+def write_csv(path, out):
+    """The sweep cells and the per-configuration rows as CSV, one row each, with status columns."""
+    import csv
+    with open(path, "w", newline="") as f:
+        wr = csv.writer(f)
+        wr.writerow(["kind", "name", "tile_m", "tile_n", "ms_per_launch", "tflops", "compulsory_GBs", "bound",
+                     "frac_of_roof", "max_abs_err", "tol", "status", "status_detail"])
+        for key, e in (out.get("tile_sweep") or {}).items():
+            tm, tn = key.split("x")
+            wr.writerow(["tile_sweep", out["config"]["workload"], tm, tn,
+                         "nan" if e["kernel_ms_avg"] is None else e["kernel_ms_avg"],
+                         "nan" if e["tflops"] is None else e["tflops"], "", "mfma",
+                         "nan" if e["frac_of_mfma_peak"] is None else e["frac_of_mfma_peak"], "", "",
+                         e["status"], e["status_detail"]])
+        for key, e in (out.get("all_workloads") or {}).items():
+            c = e.get("check") or {}
+            wr.writerow(["workload", key, e["tile"][0], e["tile"][1], e["ms_per_launch_back_to_back"], e["tflops"],
+                         e["compulsory_GBs"], e["roofline"]["bound"], e["roofline"]["frac"],
+                         c.get("max_abs_err", ""), c.get("tol", ""), e["status"], e["status_detail"]])
 
 
 def main():
@@ -452,17 +613,13 @@ def main():
         bench_bwd(pkg, torch, args, flags)
         return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    plain = shape is None and args.input_fill == "normal" and args.qk_std is None and not args.causal
     tuned = None
     if args.tune and tile is None:
         # schedule search on the workload's own tensors, before and outside the timed region
-        from paper_2603_01960_amd.workloads import make_qkv, make_workload
-        if shape is not None:
-            tq, tk, tv = make_qkv(*shape, args.dtype or "bf16", 4242)
-        else:
-            _, tq, tk, tv = make_workload(args.workload, args.dtype)
-        tile, times = pkg.tune_tile(tq.cuda(), tk.cuda(), tv.cuda(), causal=args.causal, launches=20, flags=flags)
+        _, _, tq, tk, tv = device_workload(torch, args.workload, args.dtype, args.input_fill, shape, args.qk_std)
+        tile, times = pkg.tune_tile(tq, tk, tv, causal=args.causal, launches=20, flags=flags)
         tuned = {f"{a}x{b}": round(t, 5) for (a, b), t in times.items()}
-        del tq, tk, tv
     r = time_workload(pkg, torch, args.workload, args.dtype, args.steps, args.warmup, tile, flags, args.input_fill, shape, args.qk_std)
     w, dtype = r["workload"], r["dtype"]
     flops = w.flops * (0.5 if args.causal else 1.0)     # causal: 2*B*H*S^2*D, the usual convention
@@ -472,17 +629,12 @@ def main():
 
     # which roof bounds the kernel: arithmetic intensity on compulsory bytes vs the ridge point
     comp_bytes = w.compulsory_bytes(2)
-    ridge = PEAK_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
-    if flops / comp_bytes >= ridge:
-        roofline = {"bound": "mfma", "achieved": round(kern_tflops, 2), "peak": PEAK_MFMA_TFLOPS,
-                    "unit": "TFLOP/s", "frac": round(kern_tflops / PEAK_MFMA_TFLOPS, 4)}
+    roofline = roofline_of(w, r["kernel_ms_avg"], flops)
+    # counters are committed per instantiation: one tile's traffic says nothing about another's
+    if plain and not args.linear_grid and not args.exact_max:
+        roofline["traffic"], roofline["traffic_source"] = profiled_traffic(w.name, dtype, w.D, tm, tn)
     else:
-        gbs = comp_bytes / (r["kernel_ms_avg"] * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": round(gbs / PEAK_HBM_GBS, 4)}
-    # counters are committed per tile: one tile's traffic says nothing about another's
-    profiled = not args.causal and args.input_fill == "normal" and not args.linear_grid
-    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dtype, (tm, tn))) if profiled else None
+        roofline["traffic"], roofline["traffic_source"] = None, "not the profiled configuration (flags, inputs or shape differ)"
     roofline["kernel"] = f"sdpa_fwd_kernel<{dtype},D={w.D},T_M={tm},T_N={tn}>"
     roofline["kernel_ms_avg"] = round(r["kernel_ms_avg"], 5)
     roofline["kernel_ms_median"] = round(r["kernel_ms_median"], 5)
@@ -516,52 +668,36 @@ def main():
         out["frac_of_mfma_only_ceiling_random_operands"] = round(kern_tflops / ceil["random_operands"], 4)
         out["frac_of_loop_mix_ceiling"] = round(kern_tflops / ceil["random_operands_plus_loop_mix"], 4)
         out["hbm_copy_ceiling_GBs"] = hbm_copy_ceiling(torch)
-        if roofline["bound"] == "hbm":
+        if roofline["bound"] == "hbm" or (plain and args.all_workloads):
             out["hbm_read_ceiling_GBs"] = hbm_read_ceiling(pkg, torch)
+        if roofline["bound"] == "hbm":
             out["frac_of_hbm_read_ceiling"] = round(roofline["achieved"] / out["hbm_read_ceiling_GBs"], 4)
 
     if args.sweep_tiles:
-        sweep = {}
-        for tm_ in (64, 128):
-            for tn_ in (32, 64, 128):
-                if tn_ == 128 and w.D != 64:
-                    sweep[f"{tm_}x{tn_}"] = "not offered at this head dim (register budget)"
-                    continue
-                rr = time_workload(pkg, torch, args.workload, args.dtype, max(10, args.steps // 2), 3, (tm_, tn_), flags,
-                                   args.input_fill, shape, args.qk_std)
-                tf = flops / (rr["kernel_ms_avg"] * 1e-3) / 1e12
-                sweep[f"{tm_}x{tn_}"] = {"kernel_ms_avg": round(rr["kernel_ms_avg"], 5), "tflops": round(tf, 2),
-                                         "frac_of_mfma_peak": round(tf / PEAK_MFMA_TFLOPS, 4)}
-        out["tile_sweep"] = sweep
+        out["tile_sweep"] = sweep_tiles(pkg, torch, args, w, flops, flags, shape)
 
-    if args.all_workloads:
-        others = {}
-        for name, dts in (("C1", ["f16"]), ("C2", ["f16", "bf16"]), ("C3", ["bf16"]), ("C4", ["bf16"]), ("C5", ["f16"])):
-            for dt in dts:
-                ww, ms = time_batched(pkg, torch, name, dt, max(20, args.steps), args.warmup)
-                others[f"{name}_{dt}"] = {
-                    "ms_per_launch_back_to_back": round(ms, 5),
-                    "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
-                    "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
-                if ms < 0.1:
-                    gms = time_graph_replay(pkg, torch, name, dt)
-                    others[f"{name}_{dt}"]["hip_graph_replay"] = {
-                        "ms_per_launch": round(gms, 5), "tflops": round(ww.flops / (gms * 1e-3) / 1e12, 2),
-                        "compulsory_GBs": round(ww.compulsory_bytes(2) / (gms * 1e-3) / 1e9, 1)}
-                sets = -(-(1 << 30) // int(ww.compulsory_bytes(2)))      # >= 1 GiB of distinct tensors in rotation
-                if 1 < sets <= 64:
-                    _, ms = time_batched(pkg, torch, name, dt, max(4 * sets, args.steps), args.warmup, rotate=sets)
-                    others[f"{name}_{dt}"]["cache_cold"] = {
-                        "buffer_sets_in_rotation": sets, "ms_per_launch": round(ms, 5),
-                        "tflops": round(ww.flops / (ms * 1e-3) / 1e12, 2),
-                        "compulsory_GBs": round(ww.compulsory_bytes(2) / (ms * 1e-3) / 1e9, 1)}
-        out["all_workloads"] = others
-
+    check = None
     if not args.no_cpu_baseline:
         q, k, v = r["tensors"]
-        out["cpu_baseline"] = cpu_baseline(w, q, k, v, args.cpu_seconds)
+        out["cpu_baseline"], check = cpu_baseline(torch, w, dtype, q, k, v, r["o"], args.cpu_seconds, args.causal)
+        out["max_abs_err"], out["tol"], out["rows_checked"] = check["max_abs_err"], check["tol"], check["rows_checked"]
+        out["correctness"] = check
 
+    if args.all_workloads and plain:
+        out["all_workloads"] = summarise_workloads(pkg, torch, args, check if w.name == "C4" and dtype == "bf16" else None)
+        rd = out.get("hbm_read_ceiling_GBs")
+        for e in out["all_workloads"].values():
+            if rd and e["roofline"]["bound"] == "hbm":
+                for leg in (e, e.get("hip_graph_replay"), e.get("cache_cold")):
+                    if leg:
+                        leg["roofline"]["frac_of_hbm_read_ceiling"] = round(leg["roofline"]["achieved"] / rd, 4)
+
+    if args.csv:
+        write_csv(args.csv, out)
     print(json.dumps(out), flush=True)
+    if check is not None and not (check["max_abs_err"] <= check["tol"]):
+        print(f"bench.py: output error {check['max_abs_err']} exceeds the tolerance {check['tol']}", file=sys.stderr)
+        sys.exit(4)
 
 
 if __name__ == "__main__":

@@ -37,7 +37,7 @@ enum {
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64, 96, 128 or 160                             */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
     TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}, or
-                                    tile_n = 128 at D > 64 (register and LDS budget)        */
+                                    tile_n = 128 at D = 160 (four such slots exceed the LDS) */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
     TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split, tiled_sdpa_bwd: workspace NULL,
@@ -85,7 +85,7 @@ int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *
 /*
  * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
  * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
- * {32,64} and, at D = 64, 128; tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
+ * {32,64,128} (128 not at D = 160); tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
  * tiled_sdpa_fwd uses.  The result does not depend on the tile choice beyond rounding order.
  */
 int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
@@ -97,7 +97,7 @@ int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, floa
 int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flags, int *tile_m, int *tile_n);
 
 /*
- * Schedule search (the tuning policy of Sections 4.2.2-4.2.3: a small set of tile candidates, the
+ * Schedule search (the tuning policy of Table 1 and Sections 5.5-5.6: a small set of tile candidates, the
  * best one kept per problem shape): runs the forward pass of tiled_sdpa_fwd_ex with every legal
  * (tile_m, tile_n) on the caller's tensors -- one untimed launch, then `launches` (1..1000) timed
  * ones between two HIP events on `stream` -- and reports the fastest in *tile_m, *tile_n.  Unlike
@@ -116,7 +116,7 @@ int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
 /*
  * Forward pass for Sq query rows against Skv key/value rows, with the key range optionally split
  * over several workgroups: the KV-cache / decoding shapes that the paper names as future work
- * (Section 8), and the cure for shapes whose B*H*ceil(Sq/tile_m) workgroups cannot fill the GPU.
+ * (Section 7), and the cure for shapes whose B*H*ceil(Sq/tile_m) workgroups cannot fill the GPU.
  * Each split runs the recurrence of Section 4.1.2 (Eqs. 2-4) over its own contiguous run of K/V
  * tiles and leaves its state (o, m, l) in the workspace; a second kernel combines the states with
  * the rescaling of Eqs. 3-4 and applies the final O_i = o_i / l_i.
@@ -170,7 +170,7 @@ int tiled_sdpa_fwd_gqa(const void *q, const void *k, const void *v, void *o, flo
 
 /*
  * tiled_sdpa_fwd_gqa over a KV cache whose batch entries are filled to different lengths (the
- * serving form of the KV-cache variants the paper names as future work, Section 8): k and v are
+ * serving form of the KV-cache variants the paper names as future work, Section 7): k and v are
  * [B, Hkv, Skv, D] with Skv the CAPACITY of the cache, and batch entry b holds kv_lens[b] valid key
  * rows at the front of each of its heads.
  *
@@ -193,7 +193,7 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
                            int splits, void *workspace, unsigned long long workspace_bytes);
 
 /*
- * tiled_sdpa_fwd_kvcache over a PAGED cache (the KV-cache variants of the paper's roadmap, Section 8,
+ * tiled_sdpa_fwd_kvcache over a PAGED cache (the KV-cache variants of the paper's roadmap, Section 7,
  * in the form serving systems store them): keys and values live in pages of block_rows rows that any
  * batch entry may own in any order.
  *
@@ -232,7 +232,7 @@ unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, in
 
 /*
  * Backward pass: gradients of a scalar loss with respect to q, k and v, given dout = d(loss)/d(o).
- * The paper leaves the backward pass as future work (Section 8); this is the derivative of its
+ * The paper leaves the backward pass as future work (Section 7); this is the derivative of its
  * Eq. 1 (Section 3.1), evaluated tile by tile with the probabilities recomputed from the forward
  * pass's log-sum-exp (never stored), in FP32 with 16-bit MFMA operands as in Section 4.1.3:
  *     P = exp(scale * Q K^T [+ causal mask] - lse),  dV = P^T dO,  dP = dO V^T,
@@ -245,8 +245,9 @@ unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, in
  *   workspace        : device memory, 16-byte aligned, at least tiled_sdpa_bwd_workspace_bytes(B, H, S)
  *                      bytes (two FP32 values per query row); caller-owned, used only during this call's
  *                      kernels, so calls that may overlap on the GPU need distinct workspaces.
- * Three kernels are enqueued on `stream`: row statistics, then (dK, dV), then dQ.  No sum crosses
- * workgroups, so results are deterministic.  Validation order: dtype, D, shape, empty problem, null
+ * Kernels enqueued on `stream`: row statistics, then the keys-resident gradients (one fused dK + dV
+ * pass at D = 64, a dV pass and a dK pass at D = 96, 128, 160), then dQ: three kernels at D = 64, four
+ * otherwise.  No sum crosses workgroups, so results are deterministic.  Validation order: dtype, D, shape, empty problem, null
  * pointers, alignment, scale, workspace, launch.
  */
 int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, const void *dout,
@@ -284,7 +285,8 @@ unsigned long long tiled_sdpa_bwd_workspace_bytes(int B, int H, int S);
  * that mix sustains when nothing ever waits for anything.  sink: device buffer of at least 512*256 floats, overwritten.
  * flops (host pointer, may be NULL) receives the flop count of the launch.  The Section 4.2.3
  * policy of measuring on an otherwise idle GPU applies.  Returns a status code; iters = 0 only
- * reports flops.
+ * reports flops (nothing is launched and sink may then be NULL; with iters > 0 a NULL sink is
+ * TSDPA_ERR_NULL_PTR).
  */
 int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink, double *flops,
                           void *stream);
@@ -293,7 +295,7 @@ int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, float *sink
  * Measurement aid, not part of the attention path: enqueue a kernel that reads `bytes` of device memory at
  * `src` once (8192 workgroups, each a contiguous run, four 16-byte loads per lane in flight) and writes
  * nothing but one word per workgroup into `sink` (device, at least 512*256 floats).  What a decoding step
- * (Section 8: reading the K/V cache once is all it does) can be compared with besides the published
+ * (Section 7: reading the K/V cache once is all it does) can be compared with besides the published
  * HBM figure: the rate a pure read stream sustains on this GPU.  src: device, 16-byte aligned; bytes: at
  * least 128 MiB (smaller is refused as a bad shape), the part that does not fill a whole loop trip of every
  * workgroup is not read; bytes_read (host pointer, may be NULL) receives the bytes the launch does read.

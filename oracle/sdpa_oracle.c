@@ -32,7 +32,7 @@
  *
  * sdpa_oracle_rows_kv is the same definition with Sq query rows against Skv
  * key/value rows (the KV-cache / decoding shapes of the paper's roadmap,
- * Section 8): q is [BH, Sq, D], k and v are [BH, Skv, D], and Eq. 1's score
+ * Section 7): q is [BH, Sq, D], k and v are [BH, Skv, D], and Eq. 1's score
  * matrix is Sq x Skv.  The paper defines the causal mask only for Sq = Skv;
  * the reading taken here is that the Sq queries are the LAST Sq positions of
  * the Skv-long sequence, so query row i sits at position i + (Skv - Sq) and
@@ -136,7 +136,7 @@ int sdpa_oracle_rows(const float *q, const float *k, const float *v,
 }
 
 /*
- * Backward pass (the paper's roadmap, Section 8, names it as future work and prints no formula):
+ * Backward pass (the paper's roadmap, Section 7, names it as future work and prints no formula):
  * the gradient of the scalar  Lambda = sum_{i,d} dO_id * O_id  with O from Eq. 1 (Section 3.1),
  * with respect to Q, K and V, written out row by row in float64.  Differentiating Eq. 1
  * (P = row softmax of the scaled, masked scores, O = P V):

@@ -89,7 +89,7 @@ def sdpa(q, k, v, scale=None, rows=None, return_lse=False, return_p=False, causa
 
     q: [..., Sq, D]; k, v: [..., Skv, D] (leading dims are batch/head and must
     agree; Sq = Skv = S is the paper's case, Sq != Skv the KV-cache / decoding
-    shapes of its roadmap, Section 8, where under ``causal`` the queries are the
+    shapes of its roadmap, Section 7, where under ``causal`` the queries are the
     last Sq positions of the Skv-long sequence: row i sees keys j <= i + Skv - Sq).
     scale: defaults to 1/sqrt(D) (Section 4.2.1); if given it is used
     as the float32 value the device receives, promoted to double.
@@ -203,7 +203,7 @@ def sdpa_online(q, k, v, scale=None, tile_bounds=None, return_lse=False, causal=
 def sdpa_bwd(q, k, v, dout, scale=None, causal=False, qrows=None, krows=None):
     """Gradients of sum(dout * O) with respect to q, k, v for O of Eq. 1 (Section 3.1), float64, through
     the row-by-row C routine ``sdpa_oracle_bwd`` (the paper leaves the backward pass as future work,
-    Section 8, so the formulas are the derivative of Eq. 1 written out; see the C source).
+    Section 7, so the formulas are the derivative of Eq. 1 written out; see the C source).
 
     q, k, v, dout: [..., S, D] with equal shapes.  ``qrows`` / ``krows`` optionally select the rows
     for which dq / (dk, dv) are returned.  Returns (dq [..., nq, D], dk [..., nk, D], dv [..., nk, D]).

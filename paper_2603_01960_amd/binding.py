@@ -166,10 +166,12 @@ def probe_mfma(dtype: int, random_operands, iters: int, sink=None, stream=None) 
     ``random_operands``: False/0 constant operands, True/1 random ones, 2 random ones plus the
     attention loop's LDS-read and vector-ALU mix.
 
-    With ``sink=None`` and ``iters=0`` nothing is launched (flop count only)."""
+    With ``iters=0`` nothing is launched (flop count only) and ``sink`` may be None; a launch
+    (``iters > 0``) needs a real device buffer of 512*256 floats."""
+    if sink is None and iters != 0:
+        raise ValueError("probe_mfma: iters > 0 launches a kernel that writes 512*256 floats to `sink`")
     flops = ctypes.c_double(0.0)
-    st = load_library().tiled_sdpa_probe_mfma(dtype, int(random_operands), iters,
-                                              sink if sink is not None else 0x1000, ctypes.byref(flops), stream)
+    st = load_library().tiled_sdpa_probe_mfma(dtype, int(random_operands), iters, sink, ctypes.byref(flops), stream)
     if st != 0:
         raise TiledSdpaError(st, status_string(st))
     return flops.value

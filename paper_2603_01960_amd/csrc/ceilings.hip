@@ -166,9 +166,9 @@ extern "C" int tiled_sdpa_probe_mfma(int dtype, int random_operands, int iters, 
 {
     if (dtype != TSDPA_F16 && dtype != TSDPA_BF16) return TSDPA_ERR_BAD_DTYPE;
     if (iters < 0) return TSDPA_ERR_BAD_SHAPE;
-    if (!sink) return TSDPA_ERR_NULL_PTR;
     if (flops) *flops = (double)kGrid * 4.0 * (double)iters * kMfmaPerIter * 32768.0;
-    if (iters == 0) return TSDPA_OK;
+    if (iters == 0) return TSDPA_OK;    // nothing is launched, so no sink is needed
+    if (!sink) return TSDPA_ERR_NULL_PTR;
     if (random_operands == 2) {
         if (dtype == TSDPA_BF16)
             hipLaunchKernelGGL(mfma_mix_stream<true>, dim3(kGrid), dim3(256), 0, (hipStream_t)stream, sink, iters);

@@ -1,4 +1,4 @@
-// Backward pass of tiled SDPA for gfx950 (MI355X).  The paper leaves it as future work (Section 8);
+// Backward pass of tiled SDPA for gfx950 (MI355X).  The paper leaves it as future work (Section 7);
 // what is computed is the derivative of its Eq. 1 (Section 3.1), with P recomputed tile by tile from
 // the forward pass's log-sum-exp instead of being stored, in the spirit of Section 4.1.2:
 //

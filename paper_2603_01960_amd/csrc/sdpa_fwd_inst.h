@@ -83,11 +83,11 @@ int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a, LaunchTn64 tn64
     switch (key) {
         case 64032: return launch_one<T, D, 2, 32>(a);
         case 64128:
-            if constexpr (D == 64) return launch_one<T, D, 2, 128>(a);
-            else return (int)hipErrorInvalidValue;   // 128-row K/V tiles only at D = 64 (register budget)
+            if constexpr (D <= 128) return launch_one<T, D, 2, 128>(a);
+            else return (int)hipErrorInvalidValue;   // four 128-row slots of 512-byte rows exceed the LDS
         case 128032: return launch_one<T, D, 4, 32>(a);
         case 128128:
-            if constexpr (D == 64) return launch_one<T, D, 4, 128>(a);
+            if constexpr (D <= 128) return launch_one<T, D, 4, 128>(a);
             else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }

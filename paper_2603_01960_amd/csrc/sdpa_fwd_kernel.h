@@ -122,7 +122,7 @@ __device__ __forceinline__ int remap_workgroup(int id, int N, bool linear) {
 
 // KV = false is the paper's problem: S query rows against the same S key rows, one workgroup per
 // (head, query tile), final output.  KV = true generalises it for the decoding shapes of the paper's
-// roadmap (Section 8): S query rows against Skv key rows (under the causal mask the queries are the
+// roadmap (Section 7): S query rows against Skv key rows (under the causal mask the queries are the
 // last S positions of the sequence), and the key range of every (head, query tile) cut into `splits`
 // contiguous runs of tiles, one workgroup each.  With splits > 1 a workgroup writes its unnormalised
 // state (o, m, l of Eqs. 2-4) to `ws` instead of O: o as float [BH][splits][S][D], followed by
@@ -159,7 +159,12 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     constexpr int GCPR = D / 8;                   // ... of which this many hold data
     constexpr int NLD = TN * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
     static_assert(NLD >= 1 && (TN * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
-    constexpr int NB = TN / 32, KK = D / 16, DB = D / 32;
+    // A 128-row K/V tile above D = 64 is filled and released as one tile (one barrier per 128 rows) but
+    // worked through in two halves of 64 rows, each a complete step of Eqs. 2-4: four 32-row score
+    // accumulators at once do not fit the registers beside the output accumulator of these head dims.
+    constexpr int TNS = (TN == 128 && D > 64) ? 64 : TN;   // key rows per pass through scores / softmax / PV
+    constexpr int NSUB = TN / TNS;
+    constexpr int NB = TNS / 32, KK = D / 16, DB = D / 32;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const lds_ptr lds = (lds_ptr)smem;
@@ -241,16 +246,24 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
-    int k_goff[NLD], v_goff[NLD];
+    // The swizzles repeat every 16 rows and a load instruction of the workgroup's sweep lands NW * RPI rows
+    // after the previous one, so the per-lane offsets repeat with period NG in `it`: only NG of them are
+    // kept in vector registers, the rest of the distance travels in the scalar offset.
+    constexpr int RPI = 64 / CPR;                 // tile rows filled by one load instruction
+    constexpr int PER = 16 / (NW * RPI) > 1 ? 16 / (NW * RPI) : 1;
+    constexpr int NG = NLD < PER ? NLD : PER;
+    constexpr int GSTEP = NG * NW * RPI * G::GROW; // global bytes between load instructions it and it + NG
+    static_assert(NLD <= NG || (NG * NW * RPI) % 16 == 0, "offsets must repeat with the swizzle period");
+    int k_goff[NG], v_goff[NG];
 #pragma unroll
-    for (int it = 0; it < NLD; ++it) {
+    for (int it = 0; it < NG; ++it) {
         const int p = (it * NW + wave) * 64 + lane;
         const int r = p / CPR, cp = p % CPR;
         const int kc = cp ^ G::kswz(r), vc = cp ^ (G::vswz(r) << 2);   // global chunk that belongs at LDS chunk cp
         k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
         v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
     }
-    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NLD], int j, lds_ptr dst) __attribute__((always_inline)) {
+    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NG], int j, lds_ptr dst) __attribute__((always_inline)) {
         auto rsrc = whole;
         // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
@@ -289,7 +302,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
         for (int it = 0; it < NLD; ++it)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
-                                                     goff[it], soff, 0, 0);
+                                                     goff[it % NG], soff + (it / NG) * GSTEP, 0, 0);
     };
     constexpr int KSLOT0 = 0, KSLOT1 = G::TILE, VSLOT0 = 2 * G::TILE, VSLOT1 = 3 * G::TILE;
 
@@ -359,9 +372,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 
     // Eq. 2 on one tile of scores, for the rows whose weights overflowed the limit (`over`; the two lanes
     // that share a row decide together): tile maximum, new reference and the rescale of Eqs. 3-4.
-    auto raise_reference = [&](f32x16 (&sacc)[NB], int j, auto mask_tag, bool over) __attribute__((always_inline)) {
+    auto raise_reference = [&](f32x16 (&sacc)[NB], int row0, auto mask_tag, bool over) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
-        const int key0 = j * TN + g * 4;
+        const int key0 = row0 + g * 4;
         if constexpr (MASK) {
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
@@ -390,9 +403,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     };
     // p = 2^(s*c - m_ref); Eq. 3 sums the unrounded FP32 p (this lane's share of the tile is returned),
     // the PV product uses the 16-bit rounded p, left in pb as MFMA B-operands
-    auto exponentials = [&](f32x16 (&sacc)[NB], int j, vec8 (&pb)[NB][2], auto mask_tag) __attribute__((always_inline)) {
+    auto exponentials = [&](f32x16 (&sacc)[NB], int row0, vec8 (&pb)[NB][2], auto mask_tag) __attribute__((always_inline)) {
         constexpr bool MASK = decltype(mask_tag)::value;
-        const int key0 = j * TN + g * 4;
+        const int key0 = row0 + g * 4;
         float psum[4];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -428,13 +441,14 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 
     f32x16 sacc[NB];
     vec8 pb[NB][2];
-    // weights of tile j (with the lazy reference), this lane's share of their sum added to l_run
-    auto softmax_tile = [&](int j, auto mask_tag) __attribute__((always_inline)) {
-        float ps = exponentials(sacc, j, pb, mask_tag);
+    // weights of the key rows row0 ... row0 + TNS - 1 (with the lazy reference), this lane's share of their
+    // sum added to l_run
+    auto softmax_tile = [&](int row0, auto mask_tag) __attribute__((always_inline)) {
+        float ps = exponentials(sacc, row0, pb, mask_tag);
         const bool over = !(ps <= lazy_limit);               // also catches inf (first tile) and NaN
         if (__builtin_amdgcn_ballot_w64(over) != 0) {        // wavefront-uniform and rare
-            raise_reference(sacc, j, mask_tag, over);
-            ps = exponentials(sacc, j, pb, mask_tag);
+            raise_reference(sacc, row0, mask_tag, over);
+            ps = exponentials(sacc, row0, pb, mask_tag);
         }
         l_run += ps;
     };
@@ -480,13 +494,19 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         // ahead of the other wavefronts' vector work whenever their operands are ready (+1-3 %), and
         // the PV chain, whose end releases the workgroup's barrier, goes ahead of other score chains
         // (+0.5-2 % more)
-        __builtin_amdgcn_s_setprio(1);
-        scores(PAR ? KSLOT1 : KSLOT0, sacc);
-        __builtin_amdgcn_s_setprio(0);
-        softmax_tile(j, mask_tag);
-        __builtin_amdgcn_s_setprio(2);
-        accumulate(PAR ? VSLOT1 : VSLOT0, pb);
-        __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+        for (int sub = 0; sub < NSUB; ++sub) {
+            // (halves strictly one after the other: the scheduler would otherwise start the scores of the
+            // second beside the softmax of the first and hold both sets of score accumulators)
+            if (sub > 0) __builtin_amdgcn_sched_barrier(0);
+            __builtin_amdgcn_s_setprio(1);
+            scores((PAR ? KSLOT1 : KSLOT0) + sub * TNS * G::ROW, sacc);
+            __builtin_amdgcn_s_setprio(0);
+            softmax_tile(j * TN + sub * TNS, mask_tag);
+            __builtin_amdgcn_s_setprio(2);
+            accumulate((PAR ? VSLOT1 : VSLOT0) + sub * TNS * G::ROW, pb);
+            __builtin_amdgcn_s_setprio(0);
+        }
         TSDPA_WAIT_VMCNT0();
         __syncthreads();
     };

@@ -16,10 +16,10 @@ constexpr int kVersion = 200;  // 0.2.0
 bool valid_tile(int tm, int tn, int D)
 {
     if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64 || tn == 128)) return false;
-    // 128-row K/V tiles only at D = 64: their score accumulators alone take 64 registers, which beside the
-    // output accumulator of a larger head dim no longer leaves a loop without spills (and at D = 160 four
-    // such tiles do not fit the LDS)
-    return tn != 128 || D == 64;
+    // 128-row K/V tiles up to D = 128 (above D = 64 the kernel works through such a tile in two halves, its
+    // score accumulators for 128 rows not fitting the registers beside the output accumulator); at D = 160
+    // the four tile slots would take 256 KiB of LDS
+    return tn != 128 || D <= 128;
 }
 
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
@@ -120,7 +120,7 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_BAD_DTYPE: return "bad dtype: expected TSDPA_F16 or TSDPA_BF16";
         case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64, 96, 128 or 160";
         case TSDPA_ERR_MISALIGNED: return "misaligned pointer: q, k, v, o need 16-byte, lse 4-byte alignment";
-        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64} (128 at D = 64), or both 0";
+        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128} (128 not at D = 160), or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
         case TSDPA_ERR_WORKSPACE: return "split workspace is null, misaligned or too small";

@@ -47,7 +47,7 @@ class Workload:
         return 4.0 * self.B * self.H * self.S * self.S * self.D
 
     def compulsory_bytes(self, bytes_per_elem: int = 2) -> float:
-        """Q, K, V read once and O written once (the paper's bandwidth-proxy numerator, Eq. 6)."""
+        """Q, K, V read once and O written once (the paper's bandwidth-proxy numerator, Eq. 7)."""
         return 4.0 * self.B * self.H * self.S * self.D * bytes_per_elem
 
 
@@ -88,19 +88,17 @@ def make_workload(name: str, dtype: str | None = None):
     return w, q, k, v
 
 
-def sample_rows(S: int, tile_sizes=(32, 64, 128, 256), stride: int = 509, limit: int | None = None):
-    """Query rows for sampled parity at large S: first, last, both sides of every
-    tile boundary of the given tile sizes (thinned to ``limit`` if given) and a
-    fixed stride through the rest."""
-    rows = {0, S - 1}
+def sample_rows(S: int, tile_sizes=(32, 64, 128), stride: int = 509, limit: int | None = None):
+    """Query rows for sampled parity at large S: first, last, both sides of EVERY multiple of each
+    tile size (32 = the rows of one wavefront, 64 and 128 = the query tiles), and a fixed stride
+    through the rest.  ``limit`` thins only the stride rows; boundary rows are always all kept."""
+    edge = {0, S - 1}
     for t in tile_sizes:
         for b in range(t, S, t):
-            rows.add(b - 1)
-            rows.add(b)
-    rows.update(range(0, S, stride))
-    rows = sorted(r for r in rows if 0 <= r < S)
-    if limit is not None and len(rows) > limit:
-        step = len(rows) / float(limit)
-        keep = {rows[int(i * step)] for i in range(limit)} | {0, S - 1}
-        rows = sorted(keep)
-    return rows
+            edge.add(b - 1)
+            edge.add(b)
+    extra = sorted(set(range(0, S, stride)) - edge)
+    if limit is not None and len(extra) > limit:
+        step = len(extra) / float(max(limit, 1))
+        extra = [extra[int(i * step)] for i in range(max(limit, 0))]
+    return sorted(r for r in edge.union(extra) if 0 <= r < S)

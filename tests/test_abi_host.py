@@ -73,7 +73,9 @@ P = 0x1000  # fake, aligned, never dereferenced: every case below fails validati
     (dict(tile_m=128, tile_n=0), TILE),
     (dict(tile_m=128, tile_n=256), TILE),
     (dict(D=160, tile_m=128, tile_n=128), TILE),
-    (dict(D=128, tile_m=64, tile_n=128), TILE),     # 128-row K/V tiles exist at D = 64 only
+    (dict(D=160, tile_m=64, tile_n=128), TILE),     # 128-row K/V tiles exist up to D = 128 (LDS)
+    (dict(D=128, tile_m=64, tile_n=128, S=0), OK),
+    (dict(D=96, tile_m=128, tile_n=128, S=0), OK),
     (dict(D=64, tile_m=64, tile_n=128, S=0), OK),
     (dict(D=160, tile_m=64, tile_n=64, S=0), OK),
     (dict(S=1 << 23, D=128), SHAPE),
@@ -276,6 +278,10 @@ def test_probe_validates_before_touching_the_gpu(lib):
     assert lib.tiled_sdpa_probe_mfma(1, 1, 0, P, ctypes.byref(fl), None) == OK     # iters = 0: flops only
     assert fl.value == 0.0
     assert binding.probe_mfma(binding.BF16, True, 0) == 0.0
+    # flops only needs no sink; a launch without one is refused on both sides of the boundary
+    assert lib.tiled_sdpa_probe_mfma(1, 1, 0, None, ctypes.byref(fl), None) == OK
+    with pytest.raises(ValueError):
+        binding.probe_mfma(binding.BF16, True, 10)
     # the read stream: null pointers, alignment, and a buffer too small to give every workgroup a loop trip
     assert lib.tiled_sdpa_probe_hbm_read(None, 1 << 30, P, ctypes.byref(fl), None) == NULL
     assert lib.tiled_sdpa_probe_hbm_read(P, 1 << 30, None, ctypes.byref(fl), None) == NULL
@@ -344,3 +350,20 @@ def test_header_is_plain_c_and_a_c_program_links_against_the_library(tmp_path):
     assert (int(out[0]), int(out[1])) == binding.default_tile(2, 32, 8192, 128, binding.BF16)
     assert int(out[2]) == binding.kv_default_splits(1, 8, 1, 16384, 128, binding.BF16)
     assert out[3].strip() == binding.status_string(6)
+
+
+@pytest.mark.parametrize("S", [8192, 16384, 4096, 197, 1])
+def test_sampled_rows_hold_both_sides_of_every_tile_boundary(S):
+    """The row subset of the full-size parity tests: every multiple of 32 (one wavefront's rows), 64 and
+    128 (the query tiles) has the row before it and the row at it, whatever the thinning limit."""
+    from paper_2603_01960_amd.workloads import sample_rows
+    for limit in (None, 0, 5):
+        rows = sample_rows(S, limit=limit)
+        assert rows == sorted(set(rows)) and rows[0] == 0 and rows[-1] == S - 1
+        have = set(rows)
+        for b in range(32, S, 32):
+            assert b - 1 in have and b in have, (S, b)
+        # every query tile of every tile size is therefore touched on its first and last row
+        for tm in (64, 128):
+            for t in range((S + tm - 1) // tm):
+                assert t * tm in have and min(S, (t + 1) * tm) - 1 in have

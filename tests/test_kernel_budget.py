@@ -71,13 +71,13 @@ def test_main_loop_of_the_headline_kernels_touches_no_scratch_memory(dtype, tmp_
     # the square problem (last template argument 0) on 128-row query tiles: the configurations the bench times
     checked = 0
     for name, lines in kernels.items():
-        m = re.search(r"Li128ELi4ELi(32|64)ELi\dELi0E", name)
+        m = re.search(r"Li128ELi4ELi(32|64|128)ELi\dELi0E", name)
         if not m:
             continue
         checked += 1
         n = scratch_ops_in_first_loop(lines)
         assert n == 0, f"{name}: {n} scratch accesses inside the main loop (T_N = {m.group(1)})"
-    assert checked == 2, f"expected the 128x32 and 128x64 instantiations, found {checked}"
+    assert checked == 3, f"expected the 128x32, 128x64 and 128x128 instantiations, found {checked}"
     # every instantiation has two loops (unmasked tiles, masked tiles) and nothing else: a buffer descriptor
     # the compiler takes for lane-dependent turns each of its loads into a loop over distinct descriptors
     # (this happened to the paged-cache variant and cost a quarter of its speed on short runs)

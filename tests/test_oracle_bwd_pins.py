@@ -1,6 +1,6 @@
 """Pins for the backward-pass oracle (CPU only).
 
-The paper prints no backward formula (Section 8 leaves it as future work), so the oracle's gradients
+The paper prints no backward formula (Section 7 leaves it as future work), so the oracle's gradients
 are pinned to things that do not share its derivation: (a) finite differences of a 50-digit Decimal
 evaluation of Eq. 1 itself, (b) central differences of the float64 forward definition, (c) torch CPU
 float64 autograd, (d) closed forms and invariants of the softmax Jacobian, (e) agreement of the

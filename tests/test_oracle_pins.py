@@ -453,7 +453,7 @@ def test_causal_pins_catch_planted_mask_mistakes():
     assert fails(lambda i, j: j == j)                           # no mask
 
 
-# ------------------------------------------- Sq query rows against Skv keys (decoding shapes, Section 8)
+# ------------------------------------------- Sq query rows against Skv keys (decoding shapes, Section 7)
 def _brute_force_kv(q, k, v, scale, causal):
     """Rational dot products and 50-digit exponentials for q [Sq, D] against k, v [Skv, D]; under the
     causal mask the queries are the last Sq positions of the sequence."""

@@ -121,7 +121,7 @@ def test_long_configurations_on_sampled_heads_and_rows(name, dtype):
     sampled query rows (dQ) and key rows (dK, dV)."""
     w, q, k, v = make_workload(name, dtype)
     do = make_dout(q.shape, dtype, w.seed + 50)
-    rows = sample_rows(w.S, limit=48)
+    rows = sample_rows(w.S)
     for causal in (False, True):
         say(f"[case] bwd {name} {dtype} causal={causal} full size, sampled")
         got = gpu_bwd(q, k, v, do, causal=causal)
@@ -215,7 +215,7 @@ def test_grouped_heads_at_a_long_sequence_on_sampled_rows():
     q = make_qkv(B, H, S, D, dtype, seed=64)[0]
     _, k, v = make_qkv(B, Hkv, S, D, dtype, seed=65)
     do = make_dout(q.shape, dtype, 66)
-    rows = sample_rows(S, limit=40)
+    rows = sample_rows(S)
     for causal in (False, True):
         say(f"[case] bwd grouped long S={S} causal={causal}")
         qd, kd, vd, dd = (t.cuda() for t in (q, k, v, do))

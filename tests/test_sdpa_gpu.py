@@ -24,8 +24,8 @@ TILES = [(64, 32), (64, 64), (64, 128), (128, 32), (128, 64), (128, 128)]
 
 
 def legal(tile, D):
-    """128-row K/V tiles exist at D = 64 only (register budget of the larger head dims)."""
-    return tile[1] != 128 or D == 64
+    """128-row K/V tiles exist up to D = 128 (at D = 160 four such slots exceed the LDS)."""
+    return tile[1] != 128 or D <= 128
 
 
 def expect_bad_tile(D, dtype, tile):
@@ -343,7 +343,7 @@ def test_causal_text_regime_full_and_long_context_sampled():
     w, q, k, v = make_workload("C2", "bf16")
     check(q, k, v, "bf16", causal=True, tag="C2 causal")
     w, q, k, v = make_workload("C4")
-    rows = sample_rows(w.S, limit=40)
+    rows = sample_rows(w.S)
     check(q, k, v, "bf16", causal=True, rows=rows, tag="C4 causal, sampled rows")
     check(q, k, v, "bf16", causal=True, rows=rows, tile=(64, 64), tag="C4 causal, sampled rows")
 
@@ -370,7 +370,7 @@ def test_config_C3_full():
 def _long_config(name, tiles):
     w, q, k, v = make_workload(name)
     dtype = w.dtypes[0]
-    rows = sample_rows(w.S, limit=40)
+    rows = sample_rows(w.S)
     say(f"[{name}] oracle on {len(rows)} sampled query rows x {w.BH} heads")
     qn, kn, vn = q.float().numpy(), k.float().numpy(), v.float().numpy()
     ref_o, ref_lse = orc.sdpa(qn, kn, vn, rows=rows, return_lse=True)
@@ -402,7 +402,7 @@ def test_config_C5_sampled_rows():
 
 
 def test_schedule_search_returns_a_legal_tile_and_its_timings():
-    for D, dtype, n_tiles in ((128, "bf16", 4), (64, "f16", 6)):
+    for D, dtype, n_tiles in ((128, "bf16", 6), (64, "f16", 6), (160, "bf16", 4)):
         q, k, v = (t.cuda() for t in make_qkv(2, 4, 700, D, dtype, seed=33))
         tile, times = binding.tune_tile(q, k, v, causal=(D == 64), launches=3)
         say(f"[case] tune D={D} {dtype}: {tile} {times}")

@@ -179,7 +179,7 @@ def test_long_cache_decode_full_size(dtype):
         q, k, v = make_q_kv(2, 8, Sq, 16384, 128, dtype, seed=9800 + Sq)
         check_kv(q, k, v, dtype, causal=True, tag="long cache")
     q, k, v = make_q_kv(1, 2, 8192, 8192, 128, dtype, seed=9810, std=math.sqrt(2.0))
-    rows = sample_rows(8192, limit=24)
+    rows = sample_rows(8192)
     check_kv(q, k, v, dtype, rows=rows, tag="few heads, long sequence")
     check_kv(q, k, v, dtype, rows=rows, causal=True, tag="few heads, long sequence, causal")
 
