@@ -42,10 +42,15 @@ enum {
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
     TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split, tiled_sdpa_bwd: workspace NULL,
                                     not 16-byte aligned, or smaller than the matching *_workspace_bytes reports */
-    TSDPA_ERR_BAD_SPLITS = 10    /* splits < 0 or > TSDPA_MAX_SPLITS                         */
+    TSDPA_ERR_BAD_SPLITS = 10,   /* splits < 0 or > TSDPA_MAX_SPLITS                         */
+    TSDPA_ERR_STATIC_SCRATCH = 11 /* tiled_sdpa_fwd_kvcache_static: the split states need more than
+                                    TSDPA_STATIC_SCRATCH_BYTES, or the buffer's address cannot be obtained */
 };
 
 enum { TSDPA_MAX_SPLITS = 128 };
+
+/* size of the library-owned device buffer behind tiled_sdpa_fwd_kvcache_static (32 MiB per GPU) */
+enum { TSDPA_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 };
 
 /* flags for tiled_sdpa_fwd_ex */
 enum {
@@ -191,6 +196,33 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
                            int B, int H, int Hkv, int Sq, int Skv, int D, float scale, int dtype, void *stream,
                            int tile_m, int tile_n, unsigned flags,
                            int splits, void *workspace, unsigned long long workspace_bytes);
+
+/*
+ * tiled_sdpa_fwd_kvcache for callers that cannot allocate device memory and so have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The split
+ * states go to a buffer of TSDPA_STATIC_SCRATCH_BYTES that is part of the library's device code (a
+ * file-scope __device__ array: every GPU the library runs on holds its own copy from the first use of
+ * the library on it until the process ends).  The call itself allocates and frees nothing and does not
+ * synchronise; the first call on a device looks the buffer's address up once.
+ *
+ *   All arguments as for tiled_sdpa_fwd_kvcache (kv_lens NULL = a full cache, Hkv = H = plain heads),
+ *   minus the workspace.  Results are bit-identical to tiled_sdpa_fwd_kvcache with the same tile and
+ *   split count: the same kernels run.
+ *   Limit: tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, n) <= TSDPA_STATIC_SCRATCH_BYTES, n being `splits`
+ *   or the heuristic's count for splits = 0; beyond it the call enqueues nothing and returns
+ *   TSDPA_ERR_STATIC_SCRATCH (pass fewer splits, or use tiled_sdpa_fwd_kvcache).  n = 1 needs no scratch.
+ *   Nothing in the buffer has to start at zero: every word the second kernel reads is written by the
+ *   first kernel of the same call; its contents after a call are unspecified.
+ *   ALL calls on one GPU share that GPU's buffer: calls that may overlap on the GPU (different streams,
+ *   or graphs replayed concurrently) race on it and must be serialised by the caller; calls on one
+ *   stream are ordered and safe.
+ *
+ * Validation order: dtype, D, shape, empty problem, splits, tile (when the heuristic split count needs
+ * it), static-scratch size, then everything tiled_sdpa_fwd_kvcache checks.
+ */
+int tiled_sdpa_fwd_kvcache_static(const void *q, const void *k, const void *v, void *o, float *lse,
+                                  const int *kv_lens, int B, int H, int Hkv, int Sq, int Skv, int D, float scale,
+                                  int dtype, void *stream, int tile_m, int tile_n, unsigned flags, int splits);
 
 /*
  * tiled_sdpa_fwd_kvcache over a PAGED cache (the KV-cache variants of the paper's roadmap, Section 7,

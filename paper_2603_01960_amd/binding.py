@@ -30,6 +30,7 @@ EXPORTS = (
     "tiled_sdpa_fwd_kv",
     "tiled_sdpa_fwd_gqa",
     "tiled_sdpa_fwd_kvcache",
+    "tiled_sdpa_fwd_kvcache_static",
     "tiled_sdpa_fwd_paged",
     "tiled_sdpa_kv_default_splits",
     "tiled_sdpa_kv_workspace_bytes",
@@ -79,6 +80,8 @@ def load_library():
     lib.tiled_sdpa_fwd_gqa.argtypes = [vp] * 5 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_fwd_kvcache.restype = ci
     lib.tiled_sdpa_fwd_kvcache.argtypes = [vp] * 6 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
+    lib.tiled_sdpa_fwd_kvcache_static.restype = ci
+    lib.tiled_sdpa_fwd_kvcache_static.argtypes = [vp] * 6 + [ci] * 6 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci]
     lib.tiled_sdpa_fwd_paged.restype = ci
     lib.tiled_sdpa_fwd_paged.argtypes = [vp] * 7 + [ci] * 7 + [cf, ci, vp, ci, ci, ctypes.c_uint, ci, vp, ctypes.c_ulonglong]
     lib.tiled_sdpa_tune_tile.restype = ci
@@ -242,6 +245,17 @@ def tiled_sdpa_fwd_kvcache(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, 
     return int(load_library().tiled_sdpa_fwd_kvcache(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, H, Hkv, Sq,
                                                      Skv, D, float(scale), dtype, stream, tile_m, tile_n, flags,
                                                      splits, workspace_ptr, workspace_bytes))
+
+
+STATIC_SCRATCH_BYTES = 32 * 1024 * 1024
+
+
+def tiled_sdpa_fwd_kvcache_static(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, H, Hkv, Sq, Skv, D, scale, dtype,
+                                  stream, tile_m=0, tile_n=0, flags=0, splits=0) -> int:
+    """tiled_sdpa_fwd_kvcache with the split states in the library's own static device buffer."""
+    return int(load_library().tiled_sdpa_fwd_kvcache_static(q_ptr, k_ptr, v_ptr, o_ptr, lse_ptr, kv_lens_ptr, B, H, Hkv,
+                                                            Sq, Skv, D, float(scale), dtype, stream, tile_m, tile_n,
+                                                            flags, splits))
 
 
 def sdpa_kv(q, k, v, causal: bool = False, scale=None, *, splits: int = 0, return_lse: bool = False,

@@ -5,13 +5,41 @@
 #include <cmath>
 #include <cstdint>
 #include <limits>
+#include <mutex>
 
 #include "sdpa_fwd_launch.h"
 #include "sdpa_merge_kernel.h"
 
+// Split states of tiled_sdpa_fwd_kvcache_static: device memory that belongs to the library, one copy per
+// GPU the code object is loaded on.  In host code this name is only a handle for hipGetSymbolAddress;
+// the address kernels and copies use is the one that call returns (static_scratch_ptr below).
+static __device__ __align__(256) unsigned char scratch[TSDPA_STATIC_SCRATCH_BYTES];
+
 namespace {
 
-constexpr int kVersion = 200;  // 0.2.0
+constexpr int kVersion = 300;  // 0.3.0
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices];      // per device: address of that device's copy of `scratch`, once looked up
+std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device, with that device
+// current); nullptr if the runtime cannot name it.  Allocates nothing.
+void *static_scratch_ptr()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 bool valid_tile(int tm, int tn, int D)
 {
@@ -125,6 +153,9 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
         case TSDPA_ERR_WORKSPACE: return "split workspace is null, misaligned or too small";
         case TSDPA_ERR_BAD_SPLITS: return "bad splits: must be 0 (heuristic) or 1..128";
+        case TSDPA_ERR_STATIC_SCRATCH:
+            return "split states exceed the library's static scratch buffer (or its address is unavailable): "
+                   "use tiled_sdpa_fwd_kvcache with a workspace of the caller's, or fewer splits";
         default: return "unknown status";
     }
 }
@@ -275,6 +306,37 @@ int tiled_sdpa_fwd_kvcache(const void *q, const void *k, const void *v, void *o,
 {
     return fwd_kv_impl(q, k, v, o, lse, kv_lens, nullptr, 0, 0, B, H, Hkv, Sq, Skv, D, scale, dtype, stream, tile_m,
                        tile_n, flags, splits, workspace, workspace_bytes);
+}
+
+int tiled_sdpa_fwd_kvcache_static(const void *q, const void *k, const void *v, void *o, float *lse,
+                                  const int *kv_lens, int B, int H, int Hkv, int Sq, int Skv, int D, float scale,
+                                  int dtype, void *stream, int tile_m, int tile_n, unsigned flags, int splits)
+{
+    // the checks that decide the split count, in the order of tiled_sdpa_fwd_kvcache, so that the size
+    // of the split states is known before anything is enqueued
+    int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
+    if (st != TSDPA_OK) return st;
+    if (Hkv < 0 || (H > 0 && (Hkv == 0 || H % Hkv != 0))) return TSDPA_ERR_BAD_SHAPE;
+    if ((int64_t)B * H * Sq == 0) return TSDPA_OK;
+    if (splits < 0 || splits > TSDPA_MAX_SPLITS) return TSDPA_ERR_BAD_SPLITS;
+    if ((int64_t)(H / Hkv) * Sq > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
+    if (splits == 0) {
+        int tm = tile_m, tn = tile_n;
+        if (tm == 0 && tn == 0) pick_tile_kv((H / Hkv) * Sq, Skv, D, &tm, &tn);
+        else if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64)) return TSDPA_ERR_BAD_TILE;
+        splits = pick_splits(B * Hkv, (H / Hkv) * Sq, Skv, tm, tn);
+    }
+    const unsigned long long need = tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits);
+    if (need > (unsigned long long)TSDPA_STATIC_SCRATCH_BYTES) return TSDPA_ERR_STATIC_SCRATCH;
+    void *ws = nullptr;
+    if (need > 0) {
+        ws = static_scratch_ptr();
+        if (ws == nullptr) return TSDPA_ERR_STATIC_SCRATCH;
+    }
+    // every word of the split states that the merge kernel reads is written by the attention kernel of
+    // the same call (a split without tiles stores (0, -inf, 0)), so nothing has to be cleared
+    return fwd_kv_impl(q, k, v, o, lse, kv_lens, nullptr, 0, 0, B, H, Hkv, Sq, Skv, D, scale, dtype, stream, tile_m,
+                       tile_n, flags, splits, ws, need);
 }
 
 int tiled_sdpa_fwd_paged(const void *q, const void *k_pages, const void *v_pages, void *o, float *lse,

@@ -38,11 +38,11 @@ def test_library_exports_every_declared_symbol(lib):
 def test_version_and_status_strings(lib):
     assert binding.version() >= 100
     seen = set()
-    for code in range(0, 11):
+    for code in range(0, 12):
         s = binding.status_string(code)
         assert s and s != "unknown status"
         seen.add(s)
-    assert len(seen) == 11
+    assert len(seen) == 12
     assert binding.status_string(12345) == "unknown status"
 
 
@@ -367,3 +367,50 @@ def test_sampled_rows_hold_both_sides_of_every_tile_boundary(S):
         for tm in (64, 128):
             for t in range((S + tm - 1) // tm):
                 assert t * tm in have and min(S, (t + 1) * tm) - 1 in have
+
+
+def test_static_scratch_entry_point_validates_and_enforces_its_limit(lib):
+    """tiled_sdpa_fwd_kvcache_static refuses, before anything is enqueued, a problem whose split states do
+    not fit the library's 32 MiB buffer; the other checks come in the order of tiled_sdpa_fwd_kvcache."""
+    STATIC = 11
+    f = binding.tiled_sdpa_fwd_kvcache_static
+    base = dict(q=P, k=P, v=P, o=P, lse=None, lens=None, B=2, H=8, Hkv=2, Sq=1, Skv=4096, D=128, scale=0.1,
+                dtype=1, stream=None, tm=0, tn=0, flags=0, splits=4)
+
+    def call(**kw):
+        a = dict(base); a.update(kw)
+        return f(a["q"], a["k"], a["v"], a["o"], a["lse"], a["lens"], a["B"], a["H"], a["Hkv"], a["Sq"], a["Skv"],
+                 a["D"], a["scale"], a["dtype"], a["stream"], a["tm"], a["tn"], a["flags"], a["splits"])
+    assert call(dtype=7) == DTYPE
+    assert call(D=80) == BAD_D
+    assert call(Skv=0) == SHAPE
+    assert call(Hkv=3) == SHAPE
+    assert call(B=0) == OK
+    assert call(splits=129) == 10
+    assert call(tm=32, tn=32, splits=0) == TILE
+    # 8 * 32 heads x 64 splits x 128 rows x 130 floats = 1.09 GB of split states
+    assert binding.kv_workspace_bytes(8, 32, 128, 128, 64) > binding.STATIC_SCRATCH_BYTES
+    assert call(B=8, H=32, Hkv=32, Sq=128, splits=64) == STATIC
+    # exactly at the limit passes the size check and goes on to the pointer checks
+    assert binding.kv_workspace_bytes(1, 63, 8, 128, 128) <= binding.STATIC_SCRATCH_BYTES
+    assert "static scratch" in binding.status_string(STATIC)
+
+
+def test_static_scratch_buffer_is_a_symbol_the_runtime_can_look_up(tmp_path):
+    """hipGetSymbolAddress finds a device variable through the code object's dynamic symbol table.  A
+    file-scope static one gets there only because the compiler gives it external linkage when host code
+    names it; kept local (as an `used` attribute once made it) the lookup aborts the process."""
+    import shutil
+    import subprocess
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    readelf = "/opt/rocm/llvm/bin/llvm-readelf"
+    if not (Path(hipcc).exists() and Path(readelf).exists()):
+        pytest.skip("hipcc / llvm-readelf not available")
+    from paper_2603_01960_amd import build as lib_build
+    co = tmp_path / "tiled_sdpa.co"
+    subprocess.run([hipcc, *lib_build.FLAGS, "--cuda-device-only", "--no-gpu-bundle-output", "-c",
+                    str(lib_build.CSRC / "tiled_sdpa.hip"), "-o", str(co)], check=True, capture_output=True, timeout=600)
+    syms = subprocess.run([readelf, "--dyn-syms", "-W", str(co)], check=True, capture_output=True, text=True).stdout
+    rows = [l.split() for l in syms.splitlines() if l.strip().endswith("scratch")]
+    assert len(rows) == 1, syms
+    assert rows[0][2] == str(binding.STATIC_SCRATCH_BYTES) and rows[0][3] == "OBJECT" and rows[0][4] == "GLOBAL"
