@@ -478,6 +478,27 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         const int blk0 = (t0 * TN) >> block_shift;
         page_next = __builtin_amdgcn_readfirstlane(pages[blk0 < max_blocks ? blk0 : 0]);
     }
+    if constexpr (KVM == 0) {
+        // A wavefront whose 32 rows all lie past the end of the sequence (the last query tile of a ragged S)
+        // has nothing to compute or store: it only takes its share of the tile loads and keeps the
+        // workgroup's barriers, leaving its SIMD's matrix and vector slots to the wavefronts that have rows.
+        if (r0 + wave * 32 >= S) {
+            load_tile(k, k_rsrc, k_goff, t0, lds + KSLOT0);
+            load_tile(v, v_rsrc, v_goff, t0, lds + VSLOT0);
+            TSDPA_WAIT_VMCNT0();
+            __syncthreads();
+            for (int jj = t0; jj < t1; ++jj) {
+                if (jj + 1 < t1) {
+                    const int odd = (jj + 1 - t0) & 1;            // slot of tile jj + 1
+                    load_tile(k, k_rsrc, k_goff, jj + 1, lds + (odd ? KSLOT1 : KSLOT0));
+                    load_tile(v, v_rsrc, v_goff, jj + 1, lds + (odd ? VSLOT1 : VSLOT0));
+                }
+                TSDPA_WAIT_VMCNT0();
+                __syncthreads();
+            }
+            return;
+        }
+    }
     load_tile(k, k_rsrc, k_goff, t0 + rot, lds + KSLOT0);
     load_tile(v, v_rsrc, v_goff, t0 + rot, lds + VSLOT0);
     TSDPA_WAIT_VMCNT0();
