@@ -277,9 +277,12 @@ unsigned long long tiled_sdpa_kv_workspace_bytes(int B, int H, int Sq, int D, in
  *   workspace        : device memory, 16-byte aligned, at least tiled_sdpa_bwd_workspace_bytes(B, H, S)
  *                      bytes (two FP32 values per query row); caller-owned, used only during this call's
  *                      kernels, so calls that may overlap on the GPU need distinct workspaces.
- * Kernels enqueued on `stream`: row statistics, then the keys-resident gradients (one fused dK + dV
- * pass at D = 64, a dV pass and a dK pass at D = 96, 128, 160), then dQ: three kernels at D = 64, four
- * otherwise.  No sum crosses workgroups, so results are deterministic.  Validation order: dtype, D, shape, empty problem, null
+ * Kernels enqueued on `stream`: row statistics (Delta_i = <dO_i, O_i> and LSE_i in log2 units); for query
+ * rows that see at most 64 keys (S <= 64, or the first 64 rows under the causal mask) a second small
+ * kernel that replaces Delta_i by its definition sum_j P_ij dP_ij in FP32 (on such rows the rounding of
+ * the 16-bit o inside <dO_i, O_i> is not attenuated by small P_ij); then the keys-resident gradients (one
+ * fused dK + dV pass at D = 64, a dV pass and a dK pass at D = 96, 128, 160), then dQ.  No sum crosses
+ * workgroups, so results are deterministic.  Validation order: dtype, D, shape, empty problem, null
  * pointers, alignment, scale, workspace, launch.
  */
 int tiled_sdpa_bwd(const void *q, const void *k, const void *v, const void *o, const void *dout,

@@ -86,6 +86,48 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 #endif
 }
 
+// Delta_i for the query rows that see at most 64 keys (the first rows under the causal mask; every row of
+// a sequence of up to 64), recomputed from its definition  Delta_i = sum_j P_ij dP_ij  in FP32, which
+// replaces what sdpa_bwd_prepare_kernel left there.  <dO_i, O_i> equals it only in exact arithmetic: O
+// arrives rounded to 16 bits, and the rounding error of the D-term sum goes into dS_ij = P_ij (dP_ij -
+// Delta_i) scaled by P_ij, which is of order 1 exactly on such rows (on a row of n comparable keys it is of
+// order 1/n).  One wavefront per row, lane j takes key j: two dot products of length D, an exponential,
+// one product, then a sum over the lanes.  Rows of more than 64 keys keep the <dO_i, O_i> form.
+constexpr int kBwdShortRow = 64;
+
+template <typename T, int D>
+__global__ void __launch_bounds__(64)
+sdpa_bwd_delta_short_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
+                            const T *__restrict__ dout, const float *__restrict__ lse2, float *__restrict__ delta,
+                            int S, int rows_per_head, int group, float scale_log2, int causal)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    using vec8 = typename Elem<T>::vec8;
+    const int head = blockIdx.x / rows_per_head;          // query head
+    const int i = blockIdx.x - head * rows_per_head;      // query row; it sees the keys 0 ... nk-1
+    const int nk = causal ? i + 1 : S;                    // at most 64: the launcher covers the first 64 rows under the mask, else sequences of up to 64
+    const int j = threadIdx.x;
+    const size_t qrow = ((size_t)head * S + i) * D;
+    const size_t krow = ((size_t)(head / group) * S + (j < nk ? j : 0)) * D;
+    float s = 0.f, dp = 0.f;
+#pragma unroll
+    for (int d8 = 0; d8 < D / 8; ++d8) {
+        const vec8 qa = *(const vec8 *)(q + qrow + d8 * 8), da = *(const vec8 *)(dout + qrow + d8 * 8);
+        const vec8 ka = *(const vec8 *)(k + krow + d8 * 8), va = *(const vec8 *)(v + krow + d8 * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            s = __builtin_fmaf((float)qa[e], (float)ka[e], s);
+            dp = __builtin_fmaf((float)da[e], (float)va[e], dp);
+        }
+    }
+    const float l2 = lse2[(size_t)head * S + i];
+    float x = j < nk ? __builtin_amdgcn_exp2f(__builtin_fmaf(s, scale_log2, -l2)) * dp : 0.f;
+#pragma unroll
+    for (int w = 32; w >= 1; w >>= 1) x += __shfl_xor(x, w, 64);
+    if (j == 0) delta[(size_t)head * S + i] = x;
+#endif
+}
+
 // BWD_DKV is the dK and dV passes in one (scores and P computed once for both): two output
 // accumulators and both resident operand sets, which fits 256 registers per lane at D = 64 only.
 enum { BWD_DQ = 0, BWD_DK = 1, BWD_DV = 2, BWD_DKV = 3 };

@@ -107,6 +107,18 @@ def test_closed_forms_on_the_device():
     assert dq.float().abs().max().item() <= 1.6e-2 and dk.float().abs().max().item() <= 1.6e-2
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("D", [64, 96, 128, 160])
+def test_rows_that_see_one_or_two_keys(D, dtype):
+    """dS = P (dP - Delta) cancels heavily on rows of one or two keys (P of order 1); there Delta comes
+    from its definition in FP32, not from the 16-bit forward output.  Many seeds, at the usual bound."""
+    for seed in range(12):
+        for S, causal in ((1, False), (2, False), (3, True), (2, True), (40, True), (64, False), (65, True), (130, True)):
+            q, k, v = make_qkv(1, 2, S, D, dtype, seed=12800 + 17 * seed + S)
+            do = make_dout(q.shape, dtype, 12900 + seed)
+            check_bwd(q, k, v, do, dtype, causal=causal, tag=f"few keys D={D} S={S} seed={seed}")
+
+
 def test_full_configurations_C2_and_C3():
     for name, dtype in (("C2", "f16"), ("C2", "bf16"), ("C3", "bf16")):
         w, q, k, v = make_workload(name, dtype)
