@@ -374,6 +374,9 @@ def _long_config(name, tiles):
     say(f"[{name}] oracle on {len(rows)} sampled query rows x {w.BH} heads")
     qn, kn, vn = q.float().numpy(), k.float().numpy(), v.float().numpy()
     ref_o, ref_lse = orc.sdpa(qn, kn, vn, rows=rows, return_lse=True)
+    # ... and EVERY row of the first and the last head (each lies in another XCD's share of the grid)
+    whole = [(0, 0), (w.B - 1, w.H - 1)]
+    ref_whole = [orc.sdpa(qn[b:b + 1, h:h + 1], kn[b:b + 1, h:h + 1], vn[b:b + 1, h:h + 1], return_lse=True) for b, h in whole]
     vmax = v.float().amax(dim=2, keepdim=True)
     vmin = v.float().amin(dim=2, keepdim=True)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
@@ -385,6 +388,9 @@ def _long_config(name, tiles):
         assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
         err = float(np.abs(o[:, :, rows].double().numpy() - ref_o).max())
         lerr = float(np.abs(lse[:, :, rows].double().numpy() - ref_lse).max())
+        for (b, h), (ro, rl) in zip(whole, ref_whole):
+            err = max(err, float(np.abs(o[b:b + 1, h:h + 1].double().numpy() - ro).max()))
+            lerr = max(lerr, float(np.abs(lse[b:b + 1, h:h + 1].double().numpy() - rl).max()))
         say(f"        max|dO|={err:.3e} (tol {TOL[dtype]:.1e}) max|dLSE|={lerr:.3e}")
         assert err <= TOL[dtype]
         assert lerr <= 5 * LSE_TOL
