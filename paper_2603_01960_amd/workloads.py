@@ -14,7 +14,7 @@ standard deviation; cast once (round-to-nearest-even) to FP16 or BF16.
 from __future__ import annotations
 
 import math
-from dataclasses import dataclass, field
+from dataclasses import dataclass
 from typing import Tuple
 
 import torch

@@ -7,7 +7,6 @@ float64 autograd, (d) closed forms and invariants of the softmax Jacobian, (e) a
 row-by-row C routine with the matrix-expression form and with row subsets, and (f) a mutation
 check: planted mistakes in a copy of the formulas must each trip at least one pin.
 """
-import math
 from decimal import Decimal, getcontext
 
 import numpy as np

@@ -5,7 +5,6 @@ The draws are fixed by the seeds below, so a failure names a reproducible case.
 """
 import random
 
-import numpy as np
 import pytest
 import torch
 

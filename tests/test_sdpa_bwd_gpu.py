@@ -5,7 +5,6 @@ rounded factors, rounded once more on output, so the error scales with the magni
 gradient tensor: max|g - ref| <= tol * max(1, max|ref|) with the forward tolerances tol = 2e-3
 (FP16) and 1.6e-2 (BF16); all outputs finite.
 """
-import math
 import sys
 
 import numpy as np
@@ -14,7 +13,7 @@ import torch
 
 from oracle import sdpa_oracle as orc
 from paper_2603_01960_amd import binding
-from paper_2603_01960_amd.workloads import WORKLOADS, make_qkv, make_workload, sample_rows
+from paper_2603_01960_amd.workloads import make_qkv, make_workload, sample_rows
 
 pytestmark = pytest.mark.gpu
 

@@ -14,7 +14,7 @@ import torch
 
 from oracle import sdpa_oracle as orc
 from paper_2603_01960_amd import binding
-from paper_2603_01960_amd.workloads import WORKLOADS, make_qkv, make_workload, sample_rows
+from paper_2603_01960_amd.workloads import make_qkv, make_workload, sample_rows
 
 pytestmark = pytest.mark.gpu
 
