@@ -103,6 +103,10 @@ def parse_args():
     ap.add_argument("--input-fill", default="normal", choices=["normal", "zeros", "ones"],
                     help="normal = the seeded workload; zeros / ones = same shapes with constant data "
                          "(clock experiment: the same instruction stream at lower switching activity)")
+    ap.add_argument("--grid", default=None, metavar="B,H",
+                    help="time the paper's workload grid (Section 4.3: S in 512..8192 x D in 64,96,128,160 x FP16/BF16 x "
+                         "causal/non-causal, 80 points) at this batch and head count (the paper's profiled shape is 1,8) "
+                         "instead of a workload; one JSON line, and CSV rows with --csv")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a device-to-device copy of --copy-mib MiB (reference for the HBM byte counters)")
     ap.add_argument("--copy-mib", type=int, default=1024)
@@ -562,6 +566,74 @@ def sweep_tiles(pkg, torch, args, w, flops, flags, shape):
     return sweep
 
 
+def bench_grid(pkg, torch, args):
+    """The 80 points of the paper's grid (Section 4.3) on seeded N(0,1) tensors: the plain entry point
+    (heuristic tile), and the Sq x Skv entry point with its heuristic key split, which is what fills the
+    GPU when B*H*ceil(S/128) is small.  Launches back to back between one pair of events."""
+    from paper_2603_01960_amd.workloads import make_qkv
+    B, H = (int(x) for x in args.grid.split(","))
+    rows = []
+    for D in (64, 96, 128, 160):
+        for S in (512, 1024, 2048, 4096, 8192):
+            for dt in ("f16", "bf16"):
+                q, k, v = (t.cuda() for t in make_qkv(B, H, S, D, dt, seed=7000 + S + D))
+                o = torch.empty_like(q)
+                code = pkg.F16 if dt == "f16" else pkg.BF16
+                for causal in (False, True):
+                    flags = pkg.binding.FLAG_CAUSAL if causal else 0
+                    flops = 4.0 * B * H * S * S * D * (0.5 if causal else 1.0)
+                    n = max(5, min(200, int(2e-3 / (flops / 800e12 + 8e-6))))
+                    splits = pkg.kv_default_splits(B, H, S, S, D, code, flags)
+                    ws = torch.empty(max(16, pkg.kv_workspace_bytes(B, H, S, D, splits)), dtype=torch.uint8, device="cuda")
+                    runs = {"fwd": lambda: pkg.sdpa(q, k, v, causal=causal, out=o),
+                            "fwd_kv": lambda: pkg.sdpa_kv(q, k, v, causal=causal, out=o, splits=splits, workspace=ws)}
+                    res, times = {}, {label: [] for label in runs}
+                    for label, run in runs.items():
+                        try:
+                            for _ in range(3):
+                                run()
+                        except pkg.binding.TiledSdpaError as exc:
+                            res[label] = {"status": "unsupported", "status_detail": str(exc), "ms": None, "tflops": None}
+                    torch.cuda.synchronize()
+                    # the two entry points alternate over three rounds (a short measurement taken right after a
+                    # pause reads slow: the clocks ramp up), the median of each is kept
+                    for _ in range(3):
+                        for label, run in runs.items():
+                            if label in res:
+                                continue
+                            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                            a.record()
+                            for _ in range(n):
+                                run()
+                            b.record()
+                            torch.cuda.synchronize()
+                            times[label].append(a.elapsed_time(b) / n)
+                    for label in runs:
+                        if label not in res:
+                            ms = statistics.median(times[label])
+                            res[label] = {"status": "ok", "status_detail": "", "ms": round(ms, 5),
+                                          "tflops": round(flops / (ms * 1e-3) / 1e12, 2)}
+                    tm, tn = pkg.binding.default_tile(B, H, S, D, code, flags)
+                    rows.append({"S": S, "D": D, "dtype": dt, "causal": causal, "tile": [tm, tn], "kv_splits": splits, **res})
+    best = max((r["fwd"]["tflops"] or 0.0) for r in rows)
+    out = {"metric": "SDPA forward TFLOP/s over the paper's workload grid (4*B*H*S^2*D / t, half under the causal mask)",
+           "value": best, "unit": "TFLOP/s (best point, plain entry point)", "n_gpus": 1, "higher_is_better": True,
+           "data": "synthetic", "config": {"workload": f"grid: B={B} H={H}, S in 512..8192, D in 64..160, f16/bf16, causal/non-causal"},
+           "paper_context": PAPER_CONTEXT, "grid": rows}
+    if args.csv:
+        import csv
+        with open(args.csv, "w", newline="") as f:
+            wr = csv.writer(f)
+            wr.writerow(["B", "H", "S", "D", "dtype", "causal", "tile_m", "tile_n", "entry", "kv_splits", "ms", "tflops", "status", "status_detail"])
+            for r in rows:
+                for entry in ("fwd", "fwd_kv"):
+                    e = r[entry]
+                    wr.writerow([B, H, r["S"], r["D"], r["dtype"], int(r["causal"]), r["tile"][0], r["tile"][1], entry,
+                                 r["kv_splits"] if entry == "fwd_kv" else 1, "nan" if e["ms"] is None else e["ms"],
+                                 "nan" if e["tflops"] is None else e["tflops"], e["status"], e["status_detail"]])
+    print(json.dumps(out), flush=True)
+
+
 def write_csv(path, out):
     """The sweep cells and the per-configuration rows as CSV, one row each, with status columns."""
     import csv
@@ -606,6 +678,9 @@ def main():
         | (pkg.binding.FLAG_EXACT_MAX if args.exact_max else 0) \
         | (pkg.binding.FLAG_CAUSAL if args.causal else 0)
 
+    if args.grid:
+        bench_grid(pkg, torch, args)
+        return
     if args.kv:
         bench_kv(pkg, torch, args, tile, flags)
         return
