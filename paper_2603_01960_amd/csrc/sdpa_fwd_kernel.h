@@ -263,7 +263,9 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
         v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
     }
-    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NG], int j, lds_ptr dst) __attribute__((always_inline)) {
+    struct TileSrc { decltype(k_rsrc) rsrc; int soff; };
+    // where tile j of a tensor is fetched from: descriptor and wavefront-uniform offset
+    auto tile_src = [&](const T *tensor, decltype(k_rsrc) whole, int j) __attribute__((always_inline)) {
         auto rsrc = whole;
         // wavefront-uniform (scalar) offset.  On gfx950 the descriptor's range check takes the scalar
         // offset into account (a parity test surrounds K and V with NaN to pin this): rows >= S fall
@@ -299,10 +301,17 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
                                                      __builtin_amdgcn_readfirstlane(valid * G::GROW), 0x00020000);
             soff = 0;
         }
+        return TileSrc{rsrc, soff};
+    };
+    // load instruction `it` (of NLD) of a tile
+    auto load_part = [&](const TileSrc &src, const int (&goff)[NG], lds_ptr dst, int it) __attribute__((always_inline)) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
+                                                 goff[it % NG], src.soff + (it / NG) * GSTEP, 0, 0);
+    };
+    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NG], int j, lds_ptr dst) __attribute__((always_inline)) {
+        const TileSrc src = tile_src(tensor, whole, j);
 #pragma unroll
-        for (int it = 0; it < NLD; ++it)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
-                                                     goff[it % NG], soff + (it / NG) * GSTEP, 0, 0);
+        for (int it = 0; it < NLD; ++it) load_part(src, goff, dst, it);
     };
     constexpr int KSLOT0 = 0, KSLOT1 = G::TILE, VSLOT0 = 2 * G::TILE, VSLOT1 = 3 * G::TILE;
 
@@ -344,7 +353,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     // scores, transposed: sacc[nb][i] = <k_row, q_col>, row = nb*32 + (i/4)*8 + g*4 + i%4, col = l32
-    auto scores = [&](int kslot, f32x16 (&sacc)[NB]) __attribute__((always_inline)) {
+    auto scores = [&](int kslot, f32x16 (&sacc)[NB], auto &&after_kstep) __attribute__((always_inline)) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
@@ -358,15 +367,20 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             for (int kk = 0; kk < KK; ++kk) kb[kk] = lds_read128(k_rptr[kk] + kslot);
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk) sacc[0] = E::mfma(__builtin_bit_cast(vec8, kb[kk]), qf[kk], sacc[0]);
+            for (int kk = 0; kk < KK; ++kk) {
+                sacc[0] = E::mfma(__builtin_bit_cast(vec8, kb[kk]), qf[kk], sacc[0]);
+                after_kstep(kk);
+            }
         } else {
 #pragma unroll
-            for (int kk = 0; kk < KK; ++kk)
+            for (int kk = 0; kk < KK; ++kk) {
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {   // nb innermost: independent accumulators alternate
                     u32x4 raw = lds_read128(k_rptr[kk] + kslot + nb * 32 * G::ROW);
                     sacc[nb] = E::mfma(__builtin_bit_cast(vec8, raw), qf[kk], sacc[nb]);
                 }
+                after_kstep(kk);
+            }
         }
     };
 
@@ -507,9 +521,22 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // tile j, followed by tile jn: PAR (alternating) selects the slots, MASK the masked code path
     auto step = [&](int j, int jn, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
-        if (jn < t1) {
-            load_tile(k, k_rsrc, k_goff, jn, lds + (PAR ? KSLOT0 : KSLOT1));
-            load_tile(v, v_rsrc, v_goff, jn, lds + (PAR ? VSLOT0 : VSLOT1));
+        // On 64-row tiles the loads of tile jn go out one at a time between the score MFMAs: direct-to-LDS
+        // loads issued back to back hold the wavefront at the issue stage while the CU's one address unit
+        // works through them, and a SIMD with one resident wavefront has nothing else to run meanwhile
+        // (one workgroup per CU: -12 % time; two or three per CU: -0.5 to -1 %).  A tile this workgroup does
+        // not need is fetched from past the end of the descriptor: no memory access, zeros written to a
+        // slot that nobody reads before the wait that ends the step.
+        constexpr bool SPREAD = NB >= 2;
+        const lds_ptr kdst = lds + (PAR ? KSLOT0 : KSLOT1), vdst = lds + (PAR ? VSLOT0 : VSLOT1);
+        const TileSrc ksrc = tile_src(k, k_rsrc, jn), vsrc = tile_src(v, v_rsrc, jn);
+        if constexpr (!SPREAD) {
+            if (jn < t1) {
+#pragma unroll
+                for (int it = 0; it < NLD; ++it) load_part(ksrc, k_goff, kdst, it);
+#pragma unroll
+                for (int it = 0; it < NLD; ++it) load_part(vsrc, v_goff, vdst, it);
+            }
         }
         // the MFMAs of a step form chains fed by LDS reads: a raised wavefront priority lets them go
         // ahead of the other wavefronts' vector work whenever their operands are ready (+1-3 %), and
@@ -521,7 +548,19 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             // second beside the softmax of the first and hold both sets of score accumulators)
             if (sub > 0) __builtin_amdgcn_sched_barrier(0);
             __builtin_amdgcn_s_setprio(1);
-            scores((PAR ? KSLOT1 : KSLOT0) + sub * TNS * G::ROW, sacc);
+            scores((PAR ? KSLOT1 : KSLOT0) + sub * TNS * G::ROW, sacc, [&](int kk) __attribute__((always_inline)) {
+                if constexpr (SPREAD) {
+                    constexpr int HOOKS = NSUB * KK, L = 2 * NLD;
+                    const int h = sub * KK + kk;
+#pragma unroll
+                    for (int i = h * L / HOOKS; i < (h + 1) * L / HOOKS; ++i) {
+                        if (i < NLD) load_part(ksrc, k_goff, kdst, i);
+                        else         load_part(vsrc, v_goff, vdst, i - NLD);
+                    }
+                    // MFMAs and loads keep this order (LDS reads, vector and scalar instructions may still move)
+                    __builtin_amdgcn_sched_barrier(0x786);
+                }
+            });
             __builtin_amdgcn_s_setprio(0);
             softmax_tile(j * TN + sub * TNS, mask_tag);
             __builtin_amdgcn_s_setprio(2);
