@@ -521,13 +521,14 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // tile j, followed by tile jn: PAR (alternating) selects the slots, MASK the masked code path
     auto step = [&](int j, int jn, auto par_tag, auto mask_tag) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_tag)::value;
-        // On 64-row tiles the loads of tile jn go out one at a time between the score MFMAs: direct-to-LDS
-        // loads issued back to back hold the wavefront at the issue stage while the CU's one address unit
-        // works through them, and a SIMD with one resident wavefront has nothing else to run meanwhile
-        // (one workgroup per CU: -12 % time; two or three per CU: -0.5 to -1 %).  A tile this workgroup does
-        // not need is fetched from past the end of the descriptor: no memory access, zeros written to a
-        // slot that nobody reads before the wait that ends the step.
-        constexpr bool SPREAD = NB >= 2;
+        // The loads of tile jn go out one at a time between the score MFMAs: direct-to-LDS loads issued back
+        // to back hold the wavefront at the issue stage while the CU's one address unit works through
+        // them, and a SIMD with one resident wavefront has nothing else to run meanwhile (one workgroup
+        // per CU: -12 % time; two or three per CU: -0.5 to -2 %; the 32-row tile at D = 160 alone is 6 %
+        // slower that way and keeps its loads at the start of the step).  A tile this workgroup does not
+        // need is fetched from past the end of the descriptor: no memory access, zeros written to a slot
+        // that nobody reads before the wait that ends the step.
+        constexpr bool SPREAD = NB >= 2 || D <= 128;
         const lds_ptr kdst = lds + (PAR ? KSLOT0 : KSLOT1), vdst = lds + (PAR ? VSLOT0 : VSLOT1);
         const TileSrc ksrc = tile_src(k, k_rsrc, jn), vsrc = tile_src(v, v_rsrc, jn);
         if constexpr (!SPREAD) {
