@@ -234,12 +234,15 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         const int gc = cp ^ G::swz(r);            // global chunk that belongs at LDS chunk cp
         goff[it] = gc < GCPR ? r * G::GROW + (gc << 4) : kNoFetch;
     }
-    auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) __attribute__((always_inline)) {
+    // load instruction `it` (of NLD) of tile j of a streamed tensor
+    auto load_part = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst, int it) __attribute__((always_inline)) {
         const int soff = (j < j1 ? j : nT) * G::GTILE;    // a tile past the range: outside the descriptor, zeros
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
+                                                 goff[it], soff, 0, 0);
+    };
+    auto load_tile = [&](decltype(t1_rsrc) rsrc, int j, lds_ptr dst) __attribute__((always_inline)) {
 #pragma unroll
-        for (int it = 0; it < NLD; ++it)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
-                                                     goff[it], soff, 0, 0);
+        for (int it = 0; it < NLD; ++it) load_part(rsrc, j, dst, it);
     };
     constexpr int T2BASE = 2 * G::TILE;           // T1 slot s at s*TILE, T2 slot s at T2BASE + s*TILE
     constexpr int STBASE = 4 * G::TILE;           // statistics slot s at STBASE + s*STATS
@@ -288,13 +291,14 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     }
 
     // acc[i] = <T_row, R_col>, row = nb*32 + (i/4)*8 + g*4 + i%4 of the tile, col = this lane's row
-    auto products = [&](int slot, int nb, const vec8 (&rf)[KK], f32x16 &acc) __attribute__((always_inline)) {
+    auto products = [&](int slot, int nb, const vec8 (&rf)[KK], f32x16 &acc, auto &&after_mfma) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[i] = 0.f;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
             u32x4 raw = lds_read128(row_ptr[kk] + slot + nb * 32 * G::ROW);
             acc = E::mfma(__builtin_bit_cast(vec8, raw), rf[kk], acc);
+            after_mfma(kk);
         }
     };
     // out^T += T^T X, X taken from accumulator layout as B-operands (k-slots 0..3 / 4..7 of a lane <->
@@ -322,14 +326,33 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         constexpr bool MASK = decltype(mask_tag)::value;
         constexpr int cur = PAR * G::TILE, nxt = (1 - PAR) * G::TILE;
         load_stats(j + 1, nxt);
-        load_tile(t1_rsrc, j + 1, lds + nxt);
-        load_tile(t2_rsrc, j + 1, lds + T2BASE + nxt);
+        // Where a SIMD holds one wavefront, the next tile's loads go out one at a time behind the MFMAs of the
+        // first products: back to back they hold the wavefront at the issue stage while the CU's address unit
+        // works through them, and nothing else is there to run (D = 160: 5-7 % of the whole call; with two
+        // wavefronts per SIMD the spread-out form is level without the causal mask and 4-6 % slower with it)
+        constexpr bool SPREAD = WPS == 1;
+        constexpr int HOOKS = NB * (NEED_DP ? 2 : 1) * KK, L = 2 * NLD;
+        if constexpr (!SPREAD) {
+            load_tile(t1_rsrc, j + 1, lds + nxt);
+            load_tile(t2_rsrc, j + 1, lds + T2BASE + nxt);
+        }
+        auto spread = [&](int h) __attribute__((always_inline)) {
+            if constexpr (SPREAD) {
+#pragma unroll
+                for (int i = h * L / HOOKS; i < (h + 1) * L / HOOKS; ++i) {
+                    if (i < NLD) load_part(t1_rsrc, j + 1, lds + nxt, i);
+                    else         load_part(t2_rsrc, j + 1, lds + T2BASE + nxt, i - NLD);
+                }
+                __builtin_amdgcn_sched_barrier(0x786);      // MFMAs and loads keep this order
+            }
+        };
         const int trow0 = j * TS + g * 4;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {       // one 32-row block at a time: only its accumulators are live
             f32x16 sacc, dpacc;
-            products(cur, nb, rf1, sacc);
-            if constexpr (NEED_DP) products(T2BASE + cur, nb, rf2, dpacc);
+            products(cur, nb, rf1, sacc, [&](int kk) __attribute__((always_inline)) { spread(nb * (NEED_DP ? 2 : 1) * KK + kk); });
+            if constexpr (NEED_DP)
+                products(T2BASE + cur, nb, rf2, dpacc, [&](int kk) __attribute__((always_inline)) { spread((nb * 2 + 1) * KK + kk); });
             // the 16 streamed rows this lane meets in the block come in 4 runs of 4 consecutive rows; in the
             // keys-resident passes their statistics are read from the LDS run by run (in the dK pass
             // scheduling barriers keep the compiler from fetching all of them ahead, which costs 32 registers)
