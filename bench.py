@@ -566,6 +566,12 @@ def sweep_tiles(pkg, torch, args, w, flops, flags, shape):
     return sweep
 
 
+# the paper's benchmark grid (Section 4.3): 4 head dims x 5 lengths x 2 dtypes x causal / non-causal = 80 points
+GRID_HEAD_DIMS = (64, 96, 128, 160)
+GRID_SEQ_LENS = (512, 1024, 2048, 4096, 8192)
+GRID_DTYPES = ("f16", "bf16")
+
+
 def bench_grid(pkg, torch, args):
     """The 80 points of the paper's grid (Section 4.3) on seeded N(0,1) tensors: the plain entry point
     (heuristic tile), and the Sq x Skv entry point with its heuristic key split, which is what fills the
@@ -573,9 +579,9 @@ def bench_grid(pkg, torch, args):
     from paper_2603_01960_amd.workloads import make_qkv
     B, H = (int(x) for x in args.grid.split(","))
     rows = []
-    for D in (64, 96, 128, 160):
-        for S in (512, 1024, 2048, 4096, 8192):
-            for dt in ("f16", "bf16"):
+    for D in GRID_HEAD_DIMS:
+        for S in GRID_SEQ_LENS:
+            for dt in GRID_DTYPES:
                 q, k, v = (t.cuda() for t in make_qkv(B, H, S, D, dt, seed=7000 + S + D))
                 o = torch.empty_like(q)
                 code = pkg.F16 if dt == "f16" else pkg.BF16

@@ -62,3 +62,11 @@ def test_the_roof_that_bounds_each_configuration():
 def test_more_than_one_gpu_is_refused_with_a_message():
     res = subprocess.run([sys.executable, str(ROOT / "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert res.returncode == 2 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
+
+
+def test_the_grid_mode_walks_the_eighty_points_of_the_papers_grid():
+    """Section 4.3: S in {512 ... 8192} x D in {64, 96, 128, 160} x FP16/BF16 x causal / non-causal."""
+    import bench
+
+    assert len(bench.GRID_HEAD_DIMS) * len(bench.GRID_SEQ_LENS) * len(bench.GRID_DTYPES) * 2 == 80
+    assert bench.GRID_HEAD_DIMS == (64, 96, 128, 160) and bench.GRID_SEQ_LENS == (512, 1024, 2048, 4096, 8192)
