@@ -48,6 +48,7 @@ enum {
 };
 
 enum { TSDPA_MAX_SPLITS = 128 };
+enum { TSDPA_TUNE_TILES = 7 };      /* candidates of tiled_sdpa_tune_tile */
 
 /* size of the library-owned device buffer behind tiled_sdpa_fwd_kvcache_static (32 MiB per GPU) */
 enum { TSDPA_STATIC_SCRATCH_BYTES = 32 * 1024 * 1024 };
@@ -90,8 +91,10 @@ int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *
 /*
  * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
  * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
- * {32,64,128} (128 not at D = 160); tile_m = tile_n = 0 selects the built-in shape heuristic, which is what
- * tiled_sdpa_fwd uses.  The result does not depend on the tile choice beyond rounding order.
+ * {32,64,128} (128 not at D = 160), or (tile_m, tile_n) = (256, 64), which is not in the paper's grid: eight
+ * wavefronts share every K/V tile, the fastest schedule on this GPU for long sequences at D >= 96.
+ * tile_m = tile_n = 0 selects the built-in shape heuristic, which is what tiled_sdpa_fwd uses.  The
+ * result does not depend on the tile choice beyond rounding order.
  */
 int tiled_sdpa_fwd_ex(const void *q, const void *k, const void *v, void *o, float *lse,
                       int B, int H, int S, int D, float scale, int dtype, void *stream,
@@ -108,8 +111,8 @@ int tiled_sdpa_default_tile(int B, int H, int S, int D, int dtype, unsigned flag
  * ones between two HIP events on `stream` -- and reports the fastest in *tile_m, *tile_n.  Unlike
  * every other entry point this one WAITS for the stream (once per candidate); it keeps no record, the
  * caller passes the result to tiled_sdpa_fwd_ex.  o is overwritten (with the correct result).
- * ms_per_launch: NULL, or host array of 6 floats that receives the time per launch of
- * (64,32) (64,64) (64,128) (128,32) (128,64) (128,128) in that order, -1 for a tile that is not
+ * ms_per_launch: NULL, or host array of TSDPA_TUNE_TILES (7) floats that receives the time per launch of
+ * (64,32) (64,64) (64,128) (128,32) (128,64) (128,128) (256,64) in that order, -1 for a tile that is not
  * offered at this D.  An empty problem returns the heuristic's tile and measures nothing.
  * Validation as tiled_sdpa_fwd_ex; launches out of range is TSDPA_ERR_BAD_SHAPE; tile_m or tile_n
  * NULL is TSDPA_ERR_NULL_PTR.  Timings are only meaningful on an otherwise idle GPU (Section 4.2.3).

@@ -112,7 +112,7 @@ def status_string(status: int) -> str:
     return load_library().tiled_sdpa_status_string(int(status)).decode()
 
 
-TILE_ORDER = ((64, 32), (64, 64), (64, 128), (128, 32), (128, 64), (128, 128))
+TILE_ORDER = ((64, 32), (64, 64), (64, 128), (128, 32), (128, 64), (128, 128), (256, 64))
 
 
 def tune_tile(q, k, v, causal: bool = False, scale=None, *, launches: int = 10, flags: int = 0):
@@ -131,7 +131,7 @@ def tune_tile(q, k, v, causal: bool = False, scale=None, *, launches: int = 10, 
     B, H, S, D = q.shape
     out = torch.empty_like(q)
     tm, tn = ctypes.c_int(0), ctypes.c_int(0)
-    ms = (ctypes.c_float * 6)()
+    ms = (ctypes.c_float * len(TILE_ORDER))()
     guard, stream = _guard_and_stream(torch, q.device)
     with guard:
         st = load_library().tiled_sdpa_tune_tile(q.data_ptr(), k.data_ptr(), v.data_ptr(), out.data_ptr(), B, H, S, D,

@@ -51,7 +51,9 @@ int launch_one(const LaunchArgs &a)
 template <typename T, int D>
 int launch_dispatch_tn64(int tile_m, const LaunchArgs &a)
 {
-    if (tile_m != 64 && tile_m != 128) return (int)hipErrorInvalidValue;
+    if (tile_m != 64 && tile_m != 128 && tile_m != 256) return (int)hipErrorInvalidValue;
+    // 256 query rows per workgroup (eight wavefronts, one workgroup per CU): the square problem only
+    if (tile_m == 256) return a.kv ? (int)hipErrorInvalidValue : launch_one<T, D, 8, 64>(a);
     if (a.kv && a.block_table != nullptr)
         return tile_m == 64 ? launch_one<T, D, 2, 64, 2>(a) : launch_one<T, D, 4, 64, 2>(a);
     if (a.kv)

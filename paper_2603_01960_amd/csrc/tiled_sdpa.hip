@@ -43,6 +43,8 @@ void *static_scratch_ptr()
 
 bool valid_tile(int tm, int tn, int D)
 {
+    // 256 query rows per workgroup: an addition to the paper's Table 1 grid, built for 64-row K/V tiles only
+    if (tm == 256) return tn == 64;
     if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64 || tn == 128)) return false;
     // 128-row K/V tiles up to D = 128 (above D = 64 the kernel works through such a tile in two halves, its
     // score accumulators for 128 rows not fitting the registers beside the output accumulator); at D = 160
@@ -53,9 +55,8 @@ bool valid_tile(int tm, int tn, int D)
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
 void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
 {
-    (void)BH;
-    // From the tile sweeps on MI355X: 128 query rows per workgroup (four wavefronts) win at every
-    // configuration measured.  Up to D = 128 the two K/V tile heights are within 2 % of each other on
+    // From the tile sweeps on MI355X: among the paper's query tiles, 128 rows per workgroup (four wavefronts) win
+    // at every configuration measured.  Up to D = 128 the two K/V tile heights are within 2 % of each other on
     // long sequences: 32 rows fit three wavefronts per SIMD, 64 rows halve the barriers and are built
     // with the scheduler that suits them.  The 64-row tile is ahead by 4-14 % on mid-length sequences
     // (512-2048) and under the causal mask, where the finer diagonal of the 32-row tile does not pay
@@ -66,7 +67,16 @@ void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
     *tn = 32;
     if (D == 128 && S > 64) *tn = 64;
     if (D < 128 && S >= 512) *tn = 64;
-    (void)causal;
+    // 256 query rows per workgroup (eight wavefronts share every K/V tile: half the tile loads per MFMA; one
+    // workgroup per CU) win from D = 96 upward once they give every CU a workgroup: 2-4 % at D = 96 and 128,
+    // 8-13 % at D = 160 (whose 128-row query tile has to take 32-row K/V tiles to keep two workgroups on a CU).  Not under the causal
+    // mask (four masked tiles per workgroup instead of two, and the long and short query tiles of a head
+    // balance worse: level at best, up to 2.7 times slower at D = 160), not at D = 64 (level to 7 % slower).
+    const long long wg256 = (long long)BH * ((S + 255) / 256);
+    if (!causal && D >= 96 && wg256 >= 256 && S >= (D == 160 ? 1024 : 2048)) {
+        *tm = 256;
+        *tn = 64;
+    }
 }
 
 int validate_shape(int B, int H, int S, int D, int dtype)
@@ -148,7 +158,7 @@ const char *tiled_sdpa_status_string(int status)
         case TSDPA_ERR_BAD_DTYPE: return "bad dtype: expected TSDPA_F16 or TSDPA_BF16";
         case TSDPA_ERR_UNSUPPORTED_D: return "unsupported head dimension: D must be 64, 96, 128 or 160";
         case TSDPA_ERR_MISALIGNED: return "misaligned pointer: q, k, v, o need 16-byte, lse 4-byte alignment";
-        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128} (128 not at D = 160), or both 0";
+        case TSDPA_ERR_BAD_TILE: return "bad tile: tile_m in {64,128}, tile_n in {32,64,128} (128 not at D = 160), or (256,64), or both 0";
         case TSDPA_ERR_BAD_SCALE: return "bad scale: must be finite (NaN selects 1/sqrt(D))";
         case TSDPA_ERR_LAUNCH: return "kernel launch failed";
         case TSDPA_ERR_WORKSPACE: return "split workspace is null, misaligned or too small";
@@ -179,7 +189,7 @@ int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
     if (st != TSDPA_OK) return st;
     pick_tile(B * H, S, D, (flags & TSDPA_FLAG_CAUSAL) != 0, tile_m, tile_n);
     if (ms_per_launch)
-        for (int i = 0; i < 6; ++i) ms_per_launch[i] = -1.0f;
+        for (int i = 0; i < TSDPA_TUNE_TILES; ++i) ms_per_launch[i] = -1.0f;
     if ((int64_t)B * H * S == 0) return TSDPA_OK;
     if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
     if ((((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o) & 15u) != 0) return TSDPA_ERR_MISALIGNED;
@@ -187,11 +197,12 @@ int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return TSDPA_ERR_LAUNCH;
     if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return TSDPA_ERR_LAUNCH; }
-    static const int tms[2] = {64, 128}, tns[3] = {32, 64, 128};
+    static const int tms[TSDPA_TUNE_TILES] = {64, 64, 64, 128, 128, 128, 256};
+    static const int tns[TSDPA_TUNE_TILES] = {32, 64, 128, 32, 64, 128, 64};
     float best = -1.0f;
     st = TSDPA_OK;
-    for (int i = 0; i < 6 && st == TSDPA_OK; ++i) {
-        const int tm = tms[i / 3], tn = tns[i % 3];
+    for (int i = 0; i < TSDPA_TUNE_TILES && st == TSDPA_OK; ++i) {
+        const int tm = tms[i], tn = tns[i];
         if (!valid_tile(tm, tn, D)) continue;
         // one untimed launch (first use of an instantiation sets its attributes), then the timed run
         st = tiled_sdpa_fwd_ex(q, k, v, o, nullptr, B, H, S, D, scale, dtype, stream, tm, tn, flags);

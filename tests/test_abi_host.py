@@ -72,6 +72,9 @@ P = 0x1000  # fake, aligned, never dereferenced: every case below fails validati
     (dict(tile_m=32, tile_n=64), TILE),
     (dict(tile_m=128, tile_n=0), TILE),
     (dict(tile_m=128, tile_n=256), TILE),
+    (dict(tile_m=256, tile_n=32), TILE),           # 256 query rows come with 64-row K/V tiles only
+    (dict(tile_m=256, tile_n=128), TILE),
+    (dict(tile_m=512, tile_n=64), TILE),
     (dict(D=160, tile_m=128, tile_n=128), TILE),
     (dict(D=160, tile_m=64, tile_n=128), TILE),     # 128-row K/V tiles exist up to D = 128 (LDS)
     (dict(D=128, tile_m=64, tile_n=128, S=0), OK),
@@ -117,6 +120,7 @@ WORKSPACE, SPLITS = 9, 10
     (dict(k=None), NULL),
     (dict(v=P + 4), ALIGN),
     (dict(tile_m=128, tile_n=128), TILE),          # the general kernel has no 128-row K/V tile
+    (dict(tile_m=256, tile_n=64), TILE),           # nor the 256-row query tile
     (dict(tile_m=0, tile_n=64), TILE),
     (dict(scale=math.inf), SCALE),
     (dict(splits=-1), SPLITS),
@@ -208,7 +212,7 @@ def test_grouped_backward_entry_point_validation(lib):
 
 def test_tune_entry_point_validation(lib):
     tm, tn = ctypes.c_int(-1), ctypes.c_int(-1)
-    ms = (ctypes.c_float * 6)(*([7.0] * 6))
+    ms = (ctypes.c_float * len(binding.TILE_ORDER))(*([7.0] * len(binding.TILE_ORDER)))
     call = lambda **kw: lib.tiled_sdpa_tune_tile(kw.get("q", P), P, P, P, kw.get("B", 2), 4, kw.get("S", 300), kw.get("D", 64),
                                                  0.125, kw.get("dtype", 1), None, 0, kw.get("launches", 5),
                                                  kw.get("tm", ctypes.byref(tm)), ctypes.byref(tn), ms)
@@ -294,7 +298,15 @@ def test_default_tile_is_a_legal_tile(lib):
     for S in (1, 32, 64, 197, 1024, 16384):
         for D in (64, 96, 128, 160):
             tm, tn = binding.default_tile(2, 4, S, D, binding.BF16)
-            assert tm in (64, 128) and tn in (32, 64, 128) and not (D != 64 and tn == 128)
+            assert (tm, tn) in binding.TILE_ORDER and not (D != 64 and tn == 128)
+            ctm, ctn = binding.default_tile(2, 4, S, D, binding.BF16, binding.FLAG_CAUSAL)
+            assert ctm in (64, 128) and (ctm, ctn) in binding.TILE_ORDER        # never the 256-row tile under the mask
+    # 256 query rows per workgroup: from D = 96, without the mask, once every CU gets a workgroup
+    assert binding.default_tile(2, 32, 8192, 128, binding.BF16) == (256, 64)
+    assert binding.default_tile(2, 32, 8192, 160, binding.BF16) == (256, 64)
+    assert binding.default_tile(2, 32, 8192, 64, binding.BF16) == (128, 64)
+    assert binding.default_tile(1, 8, 4096, 128, binding.BF16) == (128, 64)     # 128 workgroups of 256 rows: too few
+    assert len(binding.TILE_ORDER) == 7
     with pytest.raises(binding.TiledSdpaError):
         binding.default_tile(1, 1, 16, 72, 0)
 

@@ -75,16 +75,16 @@ def test_main_loop_of_the_headline_kernels_touches_no_scratch_memory(dtype, tmp_
                str(src), "-o", str(asm)]
         subprocess.run(cmd, check=True, capture_output=True, timeout=600)
         kernels.update(kernels_of(asm.read_text()))
-    # the square problem (last template argument 0) on 128-row query tiles: the configurations the bench times
+    # the square problem (last template argument 0) on 128- and 256-row query tiles: the configurations the bench times
     checked = 0
     for name, lines in kernels.items():
-        m = re.search(r"Li128ELi4ELi(32|64|128)ELi\dELi0E", name)
+        m = re.search(r"Li128ELi(4|8)ELi(32|64|128)ELi\dELi0E", name)
         if not m:
             continue
         checked += 1
         n = scratch_ops_in_main_loop(lines)
-        assert n == 0, f"{name}: {n} scratch accesses inside the main loop (T_N = {m.group(1)})"
-    assert checked == 3, f"expected the 128x32, 128x64 and 128x128 instantiations, found {checked}"
+        assert n == 0, f"{name}: {n} scratch accesses inside the main loop (T_M = {32 * int(m.group(1))}, T_N = {m.group(2)})"
+    assert checked == 4, f"expected the 128x32, 128x64, 128x128 and 256x64 instantiations, found {checked}"
     # every instantiation has two loops with MFMAs (unmasked tiles, masked tiles) and, in the square problem, at
     # most one without (wavefronts past the end of a ragged sequence): a buffer descriptor the compiler takes for
     # lane-dependent turns each of its loads into a loop over distinct descriptors (this happened to the

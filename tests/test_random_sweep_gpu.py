@@ -31,6 +31,8 @@ def tiles_of(D, cache=False):
     tiles = [(64, 32), (64, 64), (128, 32), (128, 64), None]
     if D <= 128 and not cache:
         tiles += [(64, 128), (128, 128)]
+    if not cache:
+        tiles += [(256, 64)]          # the square problem only
     return tiles
 
 
