@@ -14,14 +14,16 @@ from paper_2603_01960_amd.workloads import WORKLOADS  # noqa: E402
 
 
 def test_traffic_is_read_from_the_profile_of_the_same_instantiation():
-    got, src = bench.profiled_traffic("C4", "bf16", 128, 128, 64)
+    got, src = bench.profiled_traffic("C4", "bf16", 128, 256, 64)          # the heuristic's tile on C4
     assert src == "profiles/sdpa_fwd_C4_bf16.md" and 500e6 < got < 600e6
     text = (ROOT / src).read_text()
     assert f"| total | | {got / 1e6:.1f} MB |" in text          # the figure is the file's own "total" row
+    got64, src64 = bench.profiled_traffic("C4", "bf16", 128, 128, 64)
+    assert src64.endswith("_tile_128x64.md") and 500e6 < got64 < 600e6
     got32, src32 = bench.profiled_traffic("C4", "bf16", 128, 128, 32)
     assert src32.endswith("_tile_128x32.md") and got32 != got
     # no committed counter run for that tile, dtype or head dim: no figure, and the reason says which kernel
-    for args in (("C4", "bf16", 128, 64, 32), ("C4", "f16", 128, 128, 64), ("C2", "bf16", 64, 128, 64), ("C9", "bf16", 128, 128, 64)):
+    for args in (("C4", "bf16", 128, 64, 32), ("C4", "f16", 128, 256, 64), ("C2", "bf16", 64, 128, 64), ("C9", "bf16", 128, 128, 64)):
         val, why = bench.profiled_traffic(*args)
         assert val is None and "no committed counter run" in why and f"T_M={args[3]},T_N={args[4]}" in why
     # a profile of another tile under the workload's plain name is not taken for this tile
