@@ -24,13 +24,15 @@ template <> struct BwdShape<128> { static constexpr int NW = 4, WPS[4] = {2, 2, 
 // no dP) does fit 256 registers on 32-row tiles, whose 64 KB of LDS admit a second workgroup: +12 % per call.
 template <> struct BwdShape<160> { static constexpr int NW = 4, WPS[4] = {1, 1, 2, 1}, TS[4] = {64, 32, 32, 32}; static constexpr bool FUSED_DKV = false; };
 
-template <typename T, int D, int MODE, bool GRP>
-int launch_bwd_pass(const BwdLaunchArgs &a)
+template <typename T, int D, int MODE, bool GRP, int NW>
+int launch_bwd_pass_nw(const BwdLaunchArgs &a)
 {
     using Sh = BwdShape<D>;
-    constexpr int NW = Sh::NW, TS = Sh::TS[MODE], WPS = Sh::WPS[MODE];
+    constexpr int TS = Sh::TS[MODE], WPS = Sh::WPS[MODE];
     auto kern = sdpa_bwd_kernel<T, D, NW, TS, WPS, MODE, GRP>;
-    constexpr int lds_bytes = BwdGeom<D, TS>::LDS_BYTES;
+    // tile and statistics slots during the loop, one 32 x D block per wavefront for the output transpose after it
+    constexpr int stage_bytes = NW * 32 * BwdGeom<D, TS>::ROW;
+    constexpr int lds_bytes = BwdGeom<D, TS>::LDS_BYTES > stage_bytes ? BwdGeom<D, TS>::LDS_BYTES : stage_bytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
     std::call_once(once, [&] {
@@ -45,6 +47,20 @@ int launch_bwd_pass(const BwdLaunchArgs &a)
                        (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.delta,
                        (T *)out, (T *)(MODE == BWD_DKV ? a.dv : nullptr), a.S, nR, N, a.c, a.scale, a.rsign, a.causal, a.stat_bytes, a.group);
     return (int)hipGetLastError();
+}
+
+// Eight wavefronts per workgroup (256 resident rows, one workgroup per CU) at D = 128 without the causal mask, once
+// that gives every CU a workgroup: each streamed tile is then loaded once for twice the rows, half the load
+// instructions per wavefront (+4 % on the whole call at B=2 H=32 S=8192; with the mask the coarser tiles lose 3-12 %,
+// at D = 96 and 64 the gain is 0.5-2 %, and the D = 160 passes have no registers for it).
+template <typename T, int D, int MODE, bool GRP>
+int launch_bwd_pass(const BwdLaunchArgs &a)
+{
+    if constexpr (D == 128) {
+        const long long heads = MODE == BWD_DQ ? a.BH : a.BH / a.group;
+        if (!a.causal && heads * ((a.S + 255) / 256) >= 256) return launch_bwd_pass_nw<T, D, MODE, GRP, 8>(a);
+    }
+    return launch_bwd_pass_nw<T, D, MODE, GRP, BwdShape<D>::NW>(a);
 }
 
 template <typename T, int D, bool GRP>
