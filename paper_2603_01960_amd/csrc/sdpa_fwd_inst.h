@@ -1,6 +1,6 @@
 // Instantiates the forward kernel for one (element type, head dim) over the tile grid
-// T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs), plus the general Sq x Skv / split-KV
-// variant over T_M in {64,128} x T_N in {32,64}, and provides its launcher.
+// T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs) and the 256 x 64 tile of this library's own,
+// plus the general Sq x Skv / split-KV variant over T_M in {64,128} x T_N in {32,64}, and provides its launcher.
 // The kernel table is fixed at build time: there is no JIT step to cache (Section 4.2.2).
 #pragma once
 #include <mutex>
