@@ -90,7 +90,7 @@ int launch_bwd(const BwdLaunchArgs &a)
     // rows that see at most 64 keys get Delta from its definition (see the kernel)
     const int short_rows = a.causal ? (a.S < kBwdShortRow ? a.S : kBwdShortRow) : (a.S <= kBwdShortRow ? a.S : 0);
     if (short_rows > 0) {
-        hipLaunchKernelGGL((sdpa_bwd_delta_short_kernel<T, D>), dim3((unsigned)(a.BH * short_rows)), dim3(64), 0, a.stream,
+        hipLaunchKernelGGL((sdpa_bwd_delta_short_kernel<T, D>), dim3((unsigned)a.BH), dim3(256), 0, a.stream,
                            (const T *)a.q, (const T *)a.k, (const T *)a.v, (const T *)a.dout, a.lse2, a.delta,
                            a.S, short_rows, a.group, a.scale * 1.44269504088896340736f, a.causal);
         err = (int)hipGetLastError();

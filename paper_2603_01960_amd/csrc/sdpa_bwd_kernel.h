@@ -91,40 +91,54 @@ sdpa_bwd_prepare_kernel(const T *__restrict__ o, const T *__restrict__ dout, con
 // replaces what sdpa_bwd_prepare_kernel left there.  <dO_i, O_i> equals it only in exact arithmetic: O
 // arrives rounded to 16 bits, and the rounding error of the D-term sum goes into dS_ij = P_ij (dP_ij -
 // Delta_i) scaled by P_ij, which is of order 1 exactly on such rows (on a row of n comparable keys it is of
-// order 1/n).  One wavefront per row, lane j takes key j: two dot products of length D, an exponential,
-// one product, then a sum over the lanes.  Rows of more than 64 keys keep the <dO_i, O_i> form.
+// order 1/n).  Rows of more than 64 keys keep the <dO_i, O_i> form.
+// One workgroup per query head covers its first 64 rows against its first 64 keys: each of the four
+// wavefronts takes a 32-key x 32-query block of the scores and of dP (the forward kernel's transposed MFMA
+// formulation, operands straight from global memory), weights and sums its block, and the two key blocks
+// of a query meet in the LDS.  (A first form with one wavefront per row and a lane per key took half of a
+// causal backward call on short sequences.)
 constexpr int kBwdShortRow = 64;
 
 template <typename T, int D>
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
 sdpa_bwd_delta_short_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__restrict__ v,
                             const T *__restrict__ dout, const float *__restrict__ lse2, float *__restrict__ delta,
-                            int S, int rows_per_head, int group, float scale_log2, int causal)
+                            int S, int rows, int group, float scale_log2, int causal)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
-    using vec8 = typename Elem<T>::vec8;
-    const int head = blockIdx.x / rows_per_head;          // query head
-    const int i = blockIdx.x - head * rows_per_head;      // query row; it sees the keys 0 ... nk-1
-    const int nk = causal ? i + 1 : S;                    // at most 64: the launcher covers the first 64 rows under the mask, else sequences of up to 64
-    const int j = threadIdx.x;
-    const size_t qrow = ((size_t)head * S + i) * D;
-    const size_t krow = ((size_t)(head / group) * S + (j < nk ? j : 0)) * D;
-    float s = 0.f, dp = 0.f;
+    using E = Elem<T>;
+    using vec8 = typename E::vec8;
+    constexpr int KK = D / 16;
+    __shared__ float part[2][kBwdShortRow];
+    const int head = blockIdx.x;                          // query head
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, g = lane >> 5, l32 = lane & 31;
+    const int kb = wave & 1, qb = wave >> 1;              // this wavefront's 32-key block and 32-query block
+    const int krow = kb * 32 + l32, qrow = qb * 32 + l32;
+    // rows past the end are read as the last row and left out of the sums below
+    const size_t kbase = ((size_t)(head / group) * S + (krow < S ? krow : S - 1)) * D + g * 8;
+    const size_t qbase = ((size_t)head * S + (qrow < S ? qrow : S - 1)) * D + g * 8;
+    f32x16 s, dp;
 #pragma unroll
-    for (int d8 = 0; d8 < D / 8; ++d8) {
-        const vec8 qa = *(const vec8 *)(q + qrow + d8 * 8), da = *(const vec8 *)(dout + qrow + d8 * 8);
-        const vec8 ka = *(const vec8 *)(k + krow + d8 * 8), va = *(const vec8 *)(v + krow + d8 * 8);
+    for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            s = __builtin_fmaf((float)qa[e], (float)ka[e], s);
-            dp = __builtin_fmaf((float)da[e], (float)va[e], dp);
-        }
+    for (int kk = 0; kk < KK; ++kk) {
+        const vec8 ka = *(const vec8 *)(k + kbase + kk * 16), qa = *(const vec8 *)(q + qbase + kk * 16);
+        const vec8 va = *(const vec8 *)(v + kbase + kk * 16), da = *(const vec8 *)(dout + qbase + kk * 16);
+        s = E::mfma(ka, qa, s);        // s[i] = <k_row, q_col>: key kb*32 + (i/4)*8 + g*4 + i%4, query qrow
+        dp = E::mfma(va, da, dp);      // dP likewise
     }
-    const float l2 = lse2[(size_t)head * S + i];
-    float x = j < nk ? __builtin_amdgcn_exp2f(__builtin_fmaf(s, scale_log2, -l2)) * dp : 0.f;
+    const float l2 = lse2[(size_t)head * S + (qrow < S ? qrow : S - 1)];
+    const int klim = causal ? (qrow < S - 1 ? qrow : S - 1) : S - 1;      // the keys 0 ... klim reach this query
+    float x = 0.f;
 #pragma unroll
-    for (int w = 32; w >= 1; w >>= 1) x += __shfl_xor(x, w, 64);
-    if (j == 0) delta[(size_t)head * S + i] = x;
+    for (int i = 0; i < 16; ++i) {
+        const int key = kb * 32 + (i >> 2) * 8 + g * 4 + (i & 3);
+        if (key <= klim) x += __builtin_amdgcn_exp2f(__builtin_fmaf(s[i], scale_log2, -l2)) * dp[i];
+    }
+    x += __shfl_xor(x, 32, 64);                           // the two lanes that share a query column
+    if (g == 0) part[kb][qrow] = x;
+    __syncthreads();
+    if (tid < rows) delta[(size_t)head * S + tid] = part[0][tid] + part[1][tid];
 #endif
 }
 
