@@ -118,6 +118,16 @@ def test_rows_that_see_one_or_two_keys(D, dtype):
             check_bwd(q, k, v, do, dtype, causal=causal, tag=f"few keys D={D} S={S} seed={seed}")
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_many_heads_of_a_few_hundred_rows_at_D128(dtype):
+    """At D = 128 without the causal mask the passes take 256 resident rows per workgroup once that gives 256
+    workgroups: 128 heads of 257 ... 700 rows do, with a ragged last tile, and are small enough to check in full."""
+    for B, H, S in ((8, 16, 300), (2, 64, 257), (4, 32, 545)):
+        q, k, v = make_qkv(B, H, S, 128, dtype, seed=13100 + S)
+        do = make_dout(q.shape, dtype, 13150 + S)
+        check_bwd(q, k, v, do, dtype, tag=f"wide workgroups B={B} H={H} S={S}")
+
+
 def test_full_configurations_C2_and_C3():
     for name, dtype in (("C2", "f16"), ("C2", "bf16"), ("C3", "bf16")):
         w, q, k, v = make_workload(name, dtype)
