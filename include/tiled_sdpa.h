@@ -92,7 +92,8 @@ int tiled_sdpa_fwd(const void *q, const void *k, const void *v, void *o, float *
  * Same operation with the schedule exposed (Table 1 of the paper: T_M query rows per
  * workgroup, T_N key/value rows per streamed tile).  tile_m in {64,128}, tile_n in
  * {32,64,128} (128 not at D = 160), or (tile_m, tile_n) = (256, 64), which is not in the paper's grid: eight
- * wavefronts share every K/V tile, the fastest schedule on this GPU for long sequences at D >= 96.
+ * wavefronts share every K/V tile, the fastest schedule on this GPU for long sequences at D >= 96 without the
+ * causal mask.
  * tile_m = tile_n = 0 selects the built-in shape heuristic, which is what tiled_sdpa_fwd uses.  The
  * result does not depend on the tile choice beyond rounding order.
  */

@@ -68,15 +68,13 @@ void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
     if (D == 128 && S > 64) *tn = 64;
     if (D < 128 && S >= 512) *tn = 64;
     // 256 query rows per workgroup (eight wavefronts share every K/V tile: half the tile loads per MFMA; one
-    // workgroup per CU) win from D = 96 upward once they give every CU a workgroup: 2-4 % at D = 96 and 128,
-    // 8-13 % at D = 160 (whose 128-row query tile has to take 32-row K/V tiles to keep two workgroups on a CU).
-    // Under the causal mask a workgroup streams half the tiles on average and the diagonal band is four masked
-    // tiles instead of two: there the tile needs four times as many workgroups and S >= 4096 to win (4-8 % at
-    // D = 96 and 128 on B*H = 64, S = 8192 and B*H = 16, S = 16384; 6-34 % slower at S = 2048), and at D = 160,
-    // whose masked 64-row step spills, it loses.  Not at D = 64 (level to 7 % slower).
+    // workgroup per CU) win from D = 96 upward once they give every CU a workgroup: 3 % at D = 96 and 128,
+    // 5-8 % at D = 160 (whose 128-row query tile has to take 32-row K/V tiles to keep two workgroups on a CU).
+    // Not under the causal mask (a workgroup's diagonal band is four masked tiles instead of two and the query
+    // tiles of a head balance worse: within 2 % either way at S = 8192 and 16384, 13-25 % slower at S = 2048, up to
+    // 2.7 times at D = 160, whose masked 64-row step spills), not at D = 64 (3-14 % slower).
     const long long wg256 = (long long)BH * ((S + 255) / 256);
-    const bool wide = causal ? (D == 96 || D == 128) && wg256 >= 1024 && S >= 4096
-                             : D >= 96 && wg256 >= 256 && S >= (D == 160 ? 1024 : 2048);
+    const bool wide = !causal && D >= 96 && wg256 >= 256 && S >= (D == 160 ? 1024 : 2048);
     if (wide) {
         *tm = 256;
         *tn = 64;
