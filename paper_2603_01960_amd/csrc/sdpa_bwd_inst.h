@@ -51,7 +51,7 @@ int launch_bwd_pass_nw(const BwdLaunchArgs &a)
 
 // Eight wavefronts per workgroup (256 resident rows, one workgroup per CU) at D = 128 without the causal mask, once
 // that gives every CU a workgroup: each streamed tile is then loaded once for twice the rows, half the load
-// instructions per wavefront (+4 % on the whole call at B=2 H=32 S=8192; with the mask the coarser tiles lose 3-12 %,
+// instructions per wavefront (3-4 % on the whole call from S = 2048 to 16384; with the mask the coarser tiles lose 3-12 %,
 // at D = 96 and 64 the gain is 0.5-2 %, and the D = 160 passes have no registers for it).
 template <typename T, int D, int MODE, bool GRP>
 int launch_bwd_pass(const BwdLaunchArgs &a)

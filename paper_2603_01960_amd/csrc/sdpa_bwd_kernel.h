@@ -342,7 +342,7 @@ sdpa_bwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         load_stats(j + 1, nxt);
         // Where a SIMD holds one wavefront, the next tile's loads go out one at a time behind the MFMAs of the
         // first products: back to back they hold the wavefront at the issue stage while the CU's address unit
-        // works through them, and nothing else is there to run (D = 160: 5-7 % of the whole call; with two
+        // works through them, and nothing else is there to run (D = 160: 4-6 % of the whole call; with two
         // wavefronts per SIMD the spread-out form is level without the causal mask and 4-6 % slower with it)
         constexpr bool SPREAD = WPS == 1;
         constexpr int HOOKS = NB * (NEED_DP ? 2 : 1) * KK, L = 2 * NLD;
