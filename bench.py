@@ -66,6 +66,10 @@ def parse_args():
     ap.add_argument("--workload", default="C4", help="C1..C5 (default C4: B2 H32 S8192 D128 BF16)")
     ap.add_argument("--dtype", default=None, help="f16 / bf16 (default: the workload's first dtype)")
     ap.add_argument("--shape", default=None, help="B,H,S,D: a custom shape (seeded N(0,1) inputs) instead of --workload")
+    ap.add_argument("--compare-tiles", default=None,
+                    help="T_MxT_N,T_MxT_N,...: time these tiles on the workload in one process, taking turns in alternating "
+                         "order over seven rounds (a tile measured after another finds the clocks warmed up: sequential "
+                         "timings favour whatever runs later); one JSON line with the median of each")
     ap.add_argument("--kv", default=None,
                     help="B,H,Sq,Skv,D: time the Sq x Skv / split-KV entry point (decoding shapes) instead of a workload")
     ap.add_argument("--splits", type=int, default=0, help="with --kv: splits along the key axis (0 = heuristic)")
@@ -565,6 +569,41 @@ def sweep_tiles(pkg, torch, args, w, flops, flags, shape):
     return sweep
 
 
+def compare_tiles(pkg, torch, args, flags, shape):
+    """Tiles of the same workload against each other without the bias of measuring one after the other: every
+    round times each tile once (launches back to back between one pair of events), the order reverses from round
+    to round, and the median over the rounds is reported."""
+    tiles = [tuple(int(x) for x in t.lower().split("x")) for t in args.compare_tiles.split(",")]
+    w, dtype, qd, kd, vd = device_workload(torch, args.workload, args.dtype, args.input_fill, shape, args.qk_std)
+    o = torch.empty_like(qd)
+    flops = w.flops * (0.5 if args.causal else 1.0)
+    n = max(8, min(500, int(20e-3 / (flops / 1000e12 + 6e-6))))
+    for t in tiles:
+        for _ in range(5):
+            pkg.sdpa(qd, kd, vd, out=o, tile=t, flags=flags)
+    torch.cuda.synchronize()
+    legs = {t: [] for t in tiles}
+    rounds = 7
+    for r in range(rounds):
+        for t in (tiles if r % 2 == 0 else tiles[::-1]):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(n):
+                pkg.sdpa(qd, kd, vd, out=o, tile=t, flags=flags)
+            b.record()
+            torch.cuda.synchronize()
+            legs[t].append(a.elapsed_time(b) / n)
+    med = {t: statistics.median(x) for t, x in legs.items()}
+    print(json.dumps({
+        "metric": "SDPA forward, tiles compared in alternating order", "unit": "ms per launch (median over rounds)",
+        "config": {"workload": f"{w.name}: SDPA fwd {'causal' if args.causal else 'non-causal'} B={w.B} H={w.H} S={w.S} D={w.D} {dtype}",
+                   "launches_per_leg": n, "rounds": rounds},
+        "tiles": {f"{tm}x{tn}": {"ms": round(med[(tm, tn)], 5), "tflops": round(flops / (med[(tm, tn)] * 1e-3) / 1e12, 2),
+                               "min_ms": round(min(legs[(tm, tn)]), 5), "max_ms": round(max(legs[(tm, tn)]), 5)}
+                  for tm, tn in tiles},
+        "data": "synthetic", "n_gpus": 1}))
+
+
 # the paper's benchmark grid (Section 4.3): 4 head dims x 5 lengths x 2 dtypes x causal / non-causal = 80 points
 GRID_HEAD_DIMS = (64, 96, 128, 160)
 GRID_SEQ_LENS = (512, 1024, 2048, 4096, 8192)
@@ -693,6 +732,9 @@ def main():
         bench_bwd(pkg, torch, args, flags)
         return
     shape = tuple(int(x) for x in args.shape.split(",")) if args.shape else None
+    if args.compare_tiles:
+        compare_tiles(pkg, torch, args, flags, shape)
+        return
     plain = shape is None and args.input_fill == "normal" and args.qk_std is None and not args.causal
     tuned = None
     if args.tune and tile is None:
