@@ -36,8 +36,9 @@ enum {
     TSDPA_ERR_BAD_DTYPE = 3,     /* dtype is neither TSDPA_F16 nor TSDPA_BF16               */
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64, 96, 128 or 160                             */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
-    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) not in {64,128} x {32,64,128}, or
-                                    tile_n = 128 at D = 160 (four such slots exceed the LDS) */
+    TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) neither (256,64) nor in {64,128} x {32,64,128},
+                                    tile_n = 128 at D = 160 (four such slots exceed the LDS), or a
+                                    tile the entry point does not offer                       */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */
     TSDPA_ERR_WORKSPACE = 9,     /* tiled_sdpa_fwd_kv with more than one split, tiled_sdpa_bwd: workspace NULL,
@@ -135,7 +136,7 @@ int tiled_sdpa_tune_tile(const void *q, const void *k, const void *v, void *o,
  *   flags    : TSDPA_FLAG_CAUSAL takes the Sq queries to be the LAST Sq positions of the Skv-long
  *              sequence (the paper defines the mask for Sq = Skv only): key j contributes to query
  *              row i only if j <= i + Skv - Sq.  It needs Skv >= Sq.  The other flags as above.
- *   tile_m   : 64 or 128;  tile_n : 32 or 64;  both 0 = heuristic.
+ *   tile_m   : 64 or 128;  tile_n : 32 or 64;  or (256, 64) (not with a paged cache);  both 0 = heuristic.
  *   splits   : workgroups per (head, query tile) along the key axis, 1..TSDPA_MAX_SPLITS; 0 = the
  *              value tiled_sdpa_kv_default_splits reports for this shape and these flags.
  *   workspace: device memory for the split states, 16-byte aligned, at least

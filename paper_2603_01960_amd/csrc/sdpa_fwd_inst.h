@@ -1,6 +1,7 @@
 // Instantiates the forward kernel for one (element type, head dim) over the tile grid
 // T_M in {64,128} x T_N in {32,64,128} (the paper's Table 1 knobs) and the 256 x 64 tile of this library's own,
-// plus the general Sq x Skv / split-KV variant over T_M in {64,128} x T_N in {32,64}, and provides its launcher.
+// plus the general Sq x Skv / split-KV variant over T_M in {64,128} x T_N in {32,64} (and 256 x 64 on a dense cache),
+// and provides its launcher.
 // The kernel table is fixed at build time: there is no JIT step to cache (Section 4.2.2).
 #pragma once
 #include <mutex>
@@ -52,8 +53,11 @@ template <typename T, int D>
 int launch_dispatch_tn64(int tile_m, const LaunchArgs &a)
 {
     if (tile_m != 64 && tile_m != 128 && tile_m != 256) return (int)hipErrorInvalidValue;
-    // 256 query rows per workgroup (eight wavefronts, one workgroup per CU): the square problem only
-    if (tile_m == 256) return a.kv ? (int)hipErrorInvalidValue : launch_one<T, D, 8, 64>(a);
+    // 256 query rows per workgroup (eight wavefronts, one workgroup per CU): the square problem and the dense cache
+    if (tile_m == 256) {
+        if (a.kv && a.block_table != nullptr) return (int)hipErrorInvalidValue;
+        return a.kv ? launch_one<T, D, 8, 64, 1>(a) : launch_one<T, D, 8, 64>(a);
+    }
     if (a.kv && a.block_table != nullptr)
         return tile_m == 64 ? launch_one<T, D, 2, 64, 2>(a) : launch_one<T, D, 4, 64, 2>(a);
     if (a.kv)

@@ -133,6 +133,13 @@ int validate_shape_kv(int B, int H, int Sq, int Skv, int D, int dtype, unsigned 
     return TSDPA_OK;
 }
 
+// tiles of the Sq x Skv entry points: T_M in {64,128} x T_N in {32,64}, and 256 x 64 on a dense cache
+bool valid_tile_kv(int tm, int tn, bool paged)
+{
+    if (tm == 256) return tn == 64 && !paged;
+    return (tm == 64 || tm == 128) && (tn == 32 || tn == 64);
+}
+
 void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 {
     *tm = Sq <= 64 ? 64 : 128;
@@ -336,7 +343,7 @@ int tiled_sdpa_fwd_kvcache_static(const void *q, const void *k, const void *v, v
     if (splits == 0) {
         int tm = tile_m, tn = tile_n;
         if (tm == 0 && tn == 0) pick_tile_kv((H / Hkv) * Sq, Skv, D, &tm, &tn);
-        else if (!(tm == 64 || tm == 128) || !(tn == 32 || tn == 64)) return TSDPA_ERR_BAD_TILE;
+        else if (!valid_tile_kv(tm, tn, false)) return TSDPA_ERR_BAD_TILE;
         splits = pick_splits(B * Hkv, (H / Hkv) * Sq, Skv, tm, tn);
     }
     const unsigned long long need = tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits);
@@ -394,14 +401,24 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
     if (!q || !k || !v || !o) return TSDPA_ERR_NULL_PTR;
     const uintptr_t bits = (uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)o;
     if ((bits & 15u) != 0 || (((uintptr_t)lse | (uintptr_t)kv_lens) & 3u) != 0) return TSDPA_ERR_MISALIGNED;
-    if (tile_m == 0 && tile_n == 0)
+    const bool heuristic_tile = tile_m == 0 && tile_n == 0;
+    if (heuristic_tile)
         pick_tile_kv(rows, Skv, D, &tile_m, &tile_n);
-    else if (!(tile_m == 64 || tile_m == 128) || !(tile_n == 32 || tile_n == 64))
+    else if (!valid_tile_kv(tile_m, tile_n, block_table != nullptr))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
     if (std::isinf(scale)) return TSDPA_ERR_BAD_SCALE;
     if (splits < 0 || splits > TSDPA_MAX_SPLITS) return TSDPA_ERR_BAD_SPLITS;
     if (splits == 0) splits = pick_splits(B * Hkv, rows, Skv, tile_m, tile_n);
+    // Long query blocks against a dense cache of one length, no mask, no split: the 256-row query tile of the
+    // square problem, under the same conditions (with 256 such workgroups the 128-row tile has 512 and is not
+    // split either, so the split count does not depend on this choice)
+    if (heuristic_tile && splits == 1 && block_table == nullptr && kv_lens == nullptr &&
+        !(flags & TSDPA_FLAG_CAUSAL) && D >= 96 && rows >= (D == 160 ? 1024 : 2048) &&
+        (int64_t)B * Hkv * ((rows + 255) / 256) >= 256) {
+        tile_m = 256;
+        tile_n = 64;
+    }
     if (splits > 1) {
         if (!workspace || ((uintptr_t)workspace & 15u) != 0 ||
             workspace_bytes < tiled_sdpa_kv_workspace_bytes(B, H, Sq, D, splits))

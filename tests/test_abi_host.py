@@ -120,7 +120,7 @@ WORKSPACE, SPLITS = 9, 10
     (dict(k=None), NULL),
     (dict(v=P + 4), ALIGN),
     (dict(tile_m=128, tile_n=128), TILE),          # the general kernel has no 128-row K/V tile
-    (dict(tile_m=256, tile_n=64), TILE),           # nor the 256-row query tile
+    (dict(tile_m=256, tile_n=32), TILE),           # the 256-row query tile comes with 64-row K/V tiles only
     (dict(tile_m=0, tile_n=64), TILE),
     (dict(scale=math.inf), SCALE),
     (dict(splits=-1), SPLITS),

@@ -19,7 +19,7 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f16": 2e-3, "bf16": 1.6e-2}
 LSE_TOL = 1e-4
-KV_TILES = [(64, 32), (64, 64), (128, 32), (128, 64)]
+KV_TILES = [(64, 32), (64, 64), (128, 32), (128, 64), (256, 64)]      # the last one on dense caches only
 
 
 def say(msg):
@@ -422,3 +422,26 @@ def test_paged_and_dense_caches_agree_bit_for_bit():
             assert torch.equal(dense, paged), f"Sq={Sq} causal={causal}"
         else:
             assert float((dense.float() - paged.float()).abs().max()) <= TOL["bf16"] / 4
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_long_query_blocks_without_mask_take_the_256_row_tile(dtype):
+    """B*Hkv*ceil(G*Sq/256) >= 256 query tiles of 256 rows, no mask, one cache length, no split: the heuristic's
+    choice on such shapes; checked in full on small ones (grouped heads fold G*Sq rows per key/value head, so a
+    256-row tile crosses from one query head into the next), also pinned with splits, and refused on a paged cache."""
+    for B, H, Hkv, Sq, Skv, D in ((16, 8, 4, 1100, 300, 128), (64, 2, 2, 2100, 130, 96)):
+        G = H // Hkv
+        q = make_qkv(B, H, Sq, D, dtype, seed=9700 + Sq)[0]
+        _, k, v = make_qkv(B, Hkv, Skv, D, dtype, seed=9701 + Sq)
+        ref_o, ref_lse = orc.sdpa(q.float().numpy(), np.repeat(k.float().numpy(), G, axis=1),
+                                  np.repeat(v.float().numpy(), G, axis=1), return_lse=True)
+        for tile, splits in ((None, 0), ((256, 64), 3), ((128, 64), 1)):
+            say(f"[case] long query blocks B={B} H={H} Hkv={Hkv} Sq={Sq} Skv={Skv} D={D} {dtype} tile={tile} splits={splits}")
+            o, lse = binding.sdpa_kv(q.cuda(), k.cuda(), v.cuda(), splits=splits, tile=tile, return_lse=True)
+            torch.cuda.synchronize()
+            err = float(np.abs(o.cpu().double().numpy() - ref_o).max())
+            lerr = float(np.abs(lse.cpu().double().numpy() - ref_lse).max())
+            say(f"        max|dO|={err:.3e}  max|dLSE|={lerr:.3e}")
+            assert err <= TOL[dtype] and lerr <= LSE_TOL * max(1.0, float(np.abs(ref_lse).max()) / 16.0)
+    with pytest.raises(binding.TiledSdpaError):
+        check_paged(1, 2, 1, 3, 128, dtype, [200], 64, False, 1, (256, 64))
