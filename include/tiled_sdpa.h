@@ -37,7 +37,7 @@ enum {
     TSDPA_ERR_UNSUPPORTED_D = 4, /* D is not 64, 96, 128 or 160                             */
     TSDPA_ERR_MISALIGNED = 5,    /* a tensor base is not 16-byte aligned / lse not 4-byte   */
     TSDPA_ERR_BAD_TILE = 6,      /* (tile_m, tile_n) neither (256,64) nor in {64,128} x {32,64,128},
-                                    tile_n = 128 at D = 160 (four such slots exceed the LDS), or a
+                                    tile_n = 128 at D = 160 (four such slots fill the LDS), or a
                                     tile the entry point does not offer                       */
     TSDPA_ERR_BAD_SCALE = 7,     /* scale is +-infinity                                     */
     TSDPA_ERR_LAUNCH = 8,        /* the HIP runtime refused the launch                      */

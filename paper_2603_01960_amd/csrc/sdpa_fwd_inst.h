@@ -27,7 +27,7 @@ int launch_one(const LaunchArgs &a)
     constexpr int WPS = waves_per_simd<D, NW, TN>();
     auto kern = sdpa_fwd_kernel<T, D, NW, TN, WPS, KV>;
     // K/V tile slots during the loop, one 32 x D block per wavefront for the output transpose after it
-    constexpr int stage_bytes = NW * 32 * TileGeom<D, TN>::ROW;
+    constexpr int stage_bytes = NW * 32 * TileGeom<D, TN>::OROW;
     constexpr int lds_bytes = TileGeom<D, TN>::LDS_BYTES > stage_bytes ? TileGeom<D, TN>::LDS_BYTES : stage_bytes;
     static std::once_flag once;
     static hipError_t attr_err = hipSuccess;
@@ -90,7 +90,7 @@ int launch_dispatch(int tile_m, int tile_n, const LaunchArgs &a, LaunchTn64 tn64
         case 64032: return launch_one<T, D, 2, 32>(a);
         case 64128:
             if constexpr (D <= 128) return launch_one<T, D, 2, 128>(a);
-            else return (int)hipErrorInvalidValue;   // four 128-row slots of 512-byte rows exceed the LDS
+            else return (int)hipErrorInvalidValue;   // four 128-row slots of 320-byte rows are all of a CU's LDS
         case 128032: return launch_one<T, D, 4, 32>(a);
         case 128128:
             if constexpr (D <= 128) return launch_one<T, D, 4, 128>(a);

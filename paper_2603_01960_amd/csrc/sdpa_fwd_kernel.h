@@ -88,18 +88,25 @@ __device__ __forceinline__ float pair_sum(float x) {
 //      same chunk of 16 consecutive rows; the swizzle spreads them over all 64 banks.
 //   V: 64-byte block b of row r sits at b ^ vswz(r).  The transposing read has 32 lanes fetch one
 //      64-byte block of 4 consecutive rows; the swizzle puts those on 4 x 16 distinct banks.
-// Head dims that are not a power of two (96, 160) use the LDS geometry of the next power of two
-// (DG = 128, 256): rows are DG*2 bytes apart and the chunks past D are never fetched (the lanes that
-// would fill them aim outside the buffer descriptor and receive zeros without a memory access).
+// Head dims that are not a power of two (96 and 160: 12 and 20 chunks per row) keep their rows unpadded
+// as well (COMPACT): rows 192 or 320 bytes apart start 3 or 5 quarters of the 64 banks after one another, so
+//   V needs no swizzle: 4 consecutive rows put the same 64-byte block on 4 different quarters;
+//   K: row r = 4a + b starts on quarter +-b (mod 4), and chunk c = 4*ch + cl stored at c ^ (a & 3) lands on
+//      16-byte slot 4*(ch +- b) + (cl ^ a) of the 16 that make up the 64 banks: 16 consecutive rows, 16 slots.
+// A tile in the LDS is then as long as in memory, every lane of every load instruction carries data (padded
+// to 128 or 256 columns, 25 % or 37.5 % of them would fetch nothing), and the four tile slots of D = 160 take
+// 80 KiB instead of 128 at 64 rows.  The output transpose after the loop keeps the power-of-two rows (OROW).
 template <int D, int TN> struct TileGeom {
+    static constexpr bool COMPACT = (D & (D - 1)) != 0;
     static constexpr int DG = D <= 64 ? 64 : (D <= 128 ? 128 : 256);
-    static constexpr int ROW = DG * 2;              // bytes per LDS row
+    static constexpr int ROW = COMPACT ? D * 2 : DG * 2;   // bytes per LDS row of a K or V tile
+    static constexpr int OROW = DG * 2;             // bytes per LDS row of the output transpose
     static constexpr int GROW = D * 2;              // bytes per row in global memory
     static constexpr int TILE = TN * ROW;           // bytes per K or V tile in LDS
     static constexpr int GTILE = TN * GROW;         // ... and in global memory
     static constexpr int LDS_BYTES = 4 * TILE;      // K slots 0,1 then V slots 0,1
-    static __host__ __device__ constexpr int kswz(int r) { return DG == 64 ? ((r >> 1) & 7) : (r & 15); }
-    static __host__ __device__ constexpr int vswz(int r) { return DG == 64 ? ((r >> 1) & 1) : (r & 3); }
+    static __host__ __device__ constexpr int kswz(int r) { return COMPACT ? ((r >> 2) & 3) : DG == 64 ? ((r >> 1) & 7) : (r & 15); }
+    static __host__ __device__ constexpr int vswz(int r) { return COMPACT ? 0 : DG == 64 ? ((r >> 1) & 1) : (r & 3); }
 };
 
 // Workgroup -> (head, query tile).  Hardware deals consecutive workgroup ids round-robin over the
@@ -155,10 +162,15 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     using vec4 = typename E::vec4;
     using G = TileGeom<D, TN>;
     constexpr int TM = NW * 32;
-    constexpr int CPR = G::DG / 8;                // 16-byte chunks per LDS row
+    constexpr bool COMPACT = G::COMPACT;
+    constexpr int CPR = G::ROW / 16;              // 16-byte chunks per LDS row
     constexpr int GCPR = D / 8;                   // ... of which this many hold data
-    constexpr int NLD = TN * CPR / (NW * 64);     // direct-to-LDS load instructions per wavefront per tile
-    static_assert(NLD >= 1 && (TN * CPR) % (NW * 64) == 0, "tile does not divide over the workgroup");
+    // A direct-to-LDS load instruction fills one unit: 64 consecutive chunks (1 KiB) of a tile slot.
+    constexpr int U = TN * CPR / 64;              // units per K or V tile
+    constexpr int NLD = U / NW;                   // padded rows: units of a tensor's tile per wavefront
+    constexpr int L = 2 * U / NW;                 // load instructions per wavefront per K/V tile pair
+    static_assert((TN * CPR) % 64 == 0 && L >= 1 && (2 * U) % NW == 0, "tile pair does not divide over the workgroup");
+    static_assert(COMPACT || U % NW == 0, "tile does not divide over the workgroup");
     // A 128-row K/V tile above D = 64 is filled and released as one tile (one barrier per 128 rows) but
     // worked through in two halves of 64 rows, each a complete step of Eqs. 2-4: four 32-row score
     // accumulators at once do not fit the registers beside the output accumulator of these head dims.
@@ -246,22 +258,48 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
-    // The swizzles repeat every 16 rows and a load instruction of the workgroup's sweep lands NW * RPI rows
-    // after the previous one, so the per-lane offsets repeat with period NG in `it`: only NG of them are
+    // Padded rows.  The swizzles repeat every 16 rows and a load instruction of the workgroup's sweep lands
+    // NW * RPI rows after the previous one, so the per-lane offsets repeat with period NG in `it`: only NG of them are
     // kept in vector registers, the rest of the distance travels in the scalar offset.
-    constexpr int RPI = 64 / CPR;                 // tile rows filled by one load instruction
+    constexpr int RPI = COMPACT ? 1 : 64 / CPR;   // tile rows filled by one load instruction
     constexpr int PER = 16 / (NW * RPI) > 1 ? 16 / (NW * RPI) : 1;
-    constexpr int NG = NLD < PER ? NLD : PER;
+    constexpr int NG = COMPACT ? 1 : (NLD < PER ? NLD : PER);
     constexpr int GSTEP = NG * NW * RPI * G::GROW; // global bytes between load instructions it and it + NG
-    static_assert(NLD <= NG || (NG * NW * RPI) % 16 == 0, "offsets must repeat with the swizzle period");
+    static_assert(COMPACT || NLD <= NG || (NG * NW * RPI) % 16 == 0, "offsets must repeat with the swizzle period");
     int k_goff[NG], v_goff[NG];
+    if constexpr (!COMPACT) {
 #pragma unroll
-    for (int it = 0; it < NG; ++it) {
-        const int p = (it * NW + wave) * 64 + lane;
-        const int r = p / CPR, cp = p % CPR;
-        const int kc = cp ^ G::kswz(r), vc = cp ^ (G::vswz(r) << 2);   // global chunk that belongs at LDS chunk cp
-        k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
-        v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
+        for (int it = 0; it < NG; ++it) {
+            const int p = (it * NW + wave) * 64 + lane;
+            const int r = p / CPR, cp = p % CPR;
+            const int kc = cp ^ G::kswz(r), vc = cp ^ (G::vswz(r) << 2);   // global chunk that belongs at LDS chunk cp
+            k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
+            v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
+        }
+    }
+    // Compact rows.  The units of a tile pair, K's U then V's U, are dealt round-robin: load i of this wavefront is
+    // unit i * NW + wave.  A V unit is a plain copy (chunk p of the tile in memory to chunk p of the slot); a K unit
+    // has its chunks permuted within each row, and 16 rows being CP = CPR / 4 units, the per-lane offsets of K repeat
+    // every CP units.  Where U is a multiple of NW (EVEN) a load is a K or a V load for all wavefronts alike: CP
+    // registers serve K and one serves V, the rest of the distance travels in the scalar offset.  Otherwise one load
+    // of the L is a K load for the first wavefronts and a V load for the others; then L = CP and each load has a
+    // register of its own, filled for whatever this wavefront loads there.
+    constexpr int CP = CPR / 4;
+    constexpr bool EVEN = U % NW == 0;
+    constexpr int NCG = !COMPACT ? 1 : EVEN ? (NLD < CP ? NLD : CP) : L;
+    static_assert(!COMPACT || EVEN || L <= 6, "a register per load is meant for a few loads");
+    static_assert(!COMPACT || !EVEN || NLD <= CP || (CP * NW * 64) % (16 * CPR) == 0, "offsets must repeat with the swizzle period");
+    int c_goff[NCG], cv_goff = 0;
+    if constexpr (COMPACT) {
+#pragma unroll
+        for (int i = 0; i < NCG; ++i) {
+            const int u = i * NW + wave;
+            const int p = (EVEN || u < U ? u : u - U) * 64 + lane;
+            const int r = p / CPR, cp = p % CPR;
+            const int kg = r * G::GROW + ((cp ^ G::kswz(r)) << 4);
+            c_goff[i] = (EVEN || u < U) ? kg : p * 16;
+        }
+        cv_goff = (wave * 64 + lane) * 16;
     }
     struct TileSrc { decltype(k_rsrc) rsrc; int soff; };
     // where tile j of a tensor is fetched from: descriptor and wavefront-uniform offset
@@ -303,15 +341,42 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         }
         return TileSrc{rsrc, soff};
     };
-    // load instruction `it` (of NLD) of a tile
+    // load instruction `it` (of NLD) of a tile in padded rows
     auto load_part = [&](const TileSrc &src, const int (&goff)[NG], lds_ptr dst, int it) __attribute__((always_inline)) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
                                                  goff[it % NG], src.soff + (it / NG) * GSTEP, 0, 0);
     };
-    auto load_tile = [&](const T *tensor, decltype(k_rsrc) whole, const int (&goff)[NG], int j, lds_ptr dst) __attribute__((always_inline)) {
-        const TileSrc src = tile_src(tensor, whole, j);
+    // unit `unit` of a tile in compact rows
+    auto load_unit = [&](const TileSrc &src, lds_ptr dst, int unit, int goff, int soff) __attribute__((always_inline)) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rsrc, (TSDPA_LDS void *)(dst + unit * 1024), 16, goff, src.soff + soff, 0, 0);
+    };
+    // load instruction i (of L) of the tile pair (K, V): K's come first
+    auto issue = [&](const TileSrc &ksrc, const TileSrc &vsrc, lds_ptr kdst, lds_ptr vdst, int i) __attribute__((always_inline)) {
+        if constexpr (!COMPACT) {
+            if (i < NLD) load_part(ksrc, k_goff, kdst, i);
+            else         load_part(vsrc, v_goff, vdst, i - NLD);
+        } else if constexpr (EVEN) {
+            // K: NCG units on, the offsets repeat NCG * NW units = NW * 16 rows further down (NCG = CP whenever i >= NCG)
+            if (i < NLD) load_unit(ksrc, kdst, i * NW + wave, c_goff[i % NCG], (i / NCG) * (NW * 16 * G::GROW));
+            else         load_unit(vsrc, vdst, (i - NLD) * NW + wave, cv_goff, (i - NLD) * NW * 1024);
+        } else {
+            const int u = i * NW + wave;
+            if ((i + 1) * NW <= U)  load_unit(ksrc, kdst, u, c_goff[i], 0);
+            else if (i * NW >= U)   load_unit(vsrc, vdst, u - U, c_goff[i], 0);
+            else {
+                // K for the first wavefronts, V for the others: chosen by scalar selects (a branch here would cut
+                // the chain of score MFMAs that the loads are issued between in two)
+                const bool is_k = u < U;
+                const TileSrc src{is_k ? ksrc.rsrc : vsrc.rsrc, is_k ? ksrc.soff : vsrc.soff};
+                load_unit(src, is_k ? kdst : vdst, is_k ? u : u - U, c_goff[i], 0);
+            }
+        }
+    };
+    // tile j of K and of V into the slots kdst, vdst
+    auto load_tiles = [&](int j, lds_ptr kdst, lds_ptr vdst) __attribute__((always_inline)) {
+        const TileSrc ksrc = tile_src(k, k_rsrc, j), vsrc = tile_src(v, v_rsrc, j);
 #pragma unroll
-        for (int it = 0; it < NLD; ++it) load_part(src, goff, dst, it);
+        for (int i = 0; i < L; ++i) issue(ksrc, vsrc, kdst, vdst, i);
     };
     constexpr int KSLOT0 = 0, KSLOT1 = G::TILE, VSLOT0 = 2 * G::TILE, VSLOT1 = 3 * G::TILE;
 
@@ -497,15 +562,13 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         // has nothing to compute or store: it only takes its share of the tile loads and keeps the
         // workgroup's barriers, leaving its SIMD's matrix and vector slots to the wavefronts that have rows.
         if (r0 + wave * 32 >= S) {
-            load_tile(k, k_rsrc, k_goff, t0, lds + KSLOT0);
-            load_tile(v, v_rsrc, v_goff, t0, lds + VSLOT0);
+            load_tiles(t0, lds + KSLOT0, lds + VSLOT0);
             TSDPA_WAIT_VMCNT0();
             __syncthreads();
             for (int jj = t0; jj < t1; ++jj) {
                 if (jj + 1 < t1) {
                     const int odd = (jj + 1 - t0) & 1;            // slot of tile jj + 1
-                    load_tile(k, k_rsrc, k_goff, jj + 1, lds + (odd ? KSLOT1 : KSLOT0));
-                    load_tile(v, v_rsrc, v_goff, jj + 1, lds + (odd ? VSLOT1 : VSLOT0));
+                    load_tiles(jj + 1, lds + (odd ? KSLOT1 : KSLOT0), lds + (odd ? VSLOT1 : VSLOT0));
                 }
                 TSDPA_WAIT_VMCNT0();
                 __syncthreads();
@@ -513,8 +576,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             return;
         }
     }
-    load_tile(k, k_rsrc, k_goff, t0 + rot, lds + KSLOT0);
-    load_tile(v, v_rsrc, v_goff, t0 + rot, lds + VSLOT0);
+    load_tiles(t0 + rot, lds + KSLOT0, lds + VSLOT0);
     TSDPA_WAIT_VMCNT0();
     __syncthreads();
 
@@ -534,9 +596,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         if constexpr (!SPREAD) {
             if (jn < t1) {
 #pragma unroll
-                for (int it = 0; it < NLD; ++it) load_part(ksrc, k_goff, kdst, it);
-#pragma unroll
-                for (int it = 0; it < NLD; ++it) load_part(vsrc, v_goff, vdst, it);
+                for (int i = 0; i < L; ++i) issue(ksrc, vsrc, kdst, vdst, i);
             }
         }
         // the MFMAs of a step form chains fed by LDS reads: a raised wavefront priority lets them go
@@ -551,13 +611,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             __builtin_amdgcn_s_setprio(1);
             scores((PAR ? KSLOT1 : KSLOT0) + sub * TNS * G::ROW, sacc, [&](int kk) __attribute__((always_inline)) {
                 if constexpr (SPREAD) {
-                    constexpr int HOOKS = NSUB * KK, L = 2 * NLD;
+                    constexpr int HOOKS = NSUB * KK;
                     const int h = sub * KK + kk;
 #pragma unroll
-                    for (int i = h * L / HOOKS; i < (h + 1) * L / HOOKS; ++i) {
-                        if (i < NLD) load_part(ksrc, k_goff, kdst, i);
-                        else         load_part(vsrc, v_goff, vdst, i - NLD);
-                    }
+                    for (int i = h * L / HOOKS; i < (h + 1) * L / HOOKS; ++i) issue(ksrc, vsrc, kdst, vdst, i);
                     // MFMAs and loads keep this order (LDS reads, vector and scalar instructions may still move)
                     __builtin_amdgcn_sched_barrier(0x786);
                 }
@@ -634,8 +691,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         lse[(size_t)head * S + qrow] = no_key ? -INFINITY : (m_ref + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     // (the launcher sizes the dynamic LDS for the larger of the tile slots and this staging area)
     {
-        constexpr int CMASK = CPR - 1;                // chunks per row is 8 or 16
-        const lds_ptr ow = lds + wave * (32 * G::ROW);
+        constexpr int OCPR = G::OROW / 16, CMASK = OCPR - 1;   // chunks per staging row: a power of two
+        const lds_ptr ow = lds + wave * (32 * G::OROW);
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -644,15 +701,15 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
 #pragma unroll
                 for (int e = 0; e < 4; ++e) out[e] = (T)(oacc[db][q4 * 4 + e] * inv);
                 const int chunk = db * 4 + q4;        // columns chunk*8 .. +7 (< D); this lane owns half g of it
-                *(TSDPA_LDS vec4 *)(ow + l32 * G::ROW + ((chunk ^ (l32 & CMASK)) << 4) + g * 8) = out;
+                *(TSDPA_LDS vec4 *)(ow + l32 * G::OROW + ((chunk ^ (l32 & CMASK)) << 4) + g * 8) = out;
             }
         // the region is private to this wavefront: LDS operations of one wavefront complete in order
-        constexpr int RPI = 64 / CPR;                 // rows per store instruction
+        constexpr int ORPI = 64 / OCPR;               // rows per store instruction
         const int qrow0 = qt * TM + wave * 32;
 #pragma unroll
-        for (int i = 0; i < 32 / RPI; ++i) {
-            const int r = i * RPI + lane / CPR, cc = lane % CPR;
-            const u32x4 val = lds_read128(ow + r * G::ROW + ((cc ^ (r & CMASK)) << 4));
+        for (int i = 0; i < 32 / ORPI; ++i) {
+            const int r = i * ORPI + lane / OCPR, cc = lane % OCPR;
+            const u32x4 val = lds_read128(ow + r * G::OROW + ((cc ^ (r & CMASK)) << 4));
             if (qrow0 + r < S && cc < GCPR)
                 *(u32x4 *)(o + head_off + (size_t)(qrow0 + r) * D + cc * 8) = val;
         }

@@ -55,26 +55,41 @@ bool valid_tile(int tm, int tn, int D)
 // Shape heuristic (the static counterpart of the paper's shape-aware schedule policy, Section 5.6).
 void pick_tile(int BH, int S, int D, bool causal, int *tm, int *tn)
 {
-    // From the tile sweeps on MI355X: among the paper's query tiles, 128 rows per workgroup (four wavefronts) win
-    // at every configuration measured.  Up to D = 128 the two K/V tile heights are within 2 % of each other on
+    // From the tile sweeps on MI355X (every tile of a shape timed in turn, the order reversing from round to
+    // round): among the paper's query tiles, 128 rows per workgroup (four wavefronts) win wherever a sequence is
+    // longer than two such tiles.  Up to D = 128 the two K/V tile heights are within 2 % of each other on
     // long sequences: 32 rows fit three wavefronts per SIMD, 64 rows halve the barriers and are built
     // with the scheduler that suits them.  The 64-row tile is ahead by 4-14 % on mid-length sequences
     // (512-2048) and under the causal mask, where the finer diagonal of the 32-row tile does not pay
     // for its barriers; at D = 128 its masked step also spills, so every S above one tile takes 64
-    // rows there.  Short sequences at D = 64 and 96 (S = 197, 333) are level or better on 32 rows.
-    // At D = 160 only the 32-row tile leaves room for two workgroups per CU.
+    // rows there.  Short sequences (S = 197, 333) are level or better on 32 rows at D = 64, 96 and 160.
+    // At D = 160 the 64-row tile, whose four slots of unpadded rows are 80 KiB and leave room for two workgroups
+    // per CU, is 3-5 % ahead under the mask and 5-20 % ahead without it from S = 512 up to where the 256-row
+    // tile below takes over.
     *tm = S <= 64 ? 64 : 128;
     *tn = 32;
     if (D == 128 && S > 64) *tn = 64;
-    if (D < 128 && S >= 512) *tn = 64;
+    if (D != 128 && S >= 512) *tn = 64;
+    // up to two 128-row tiles per head and fewer of them than CUs: 64 query rows per workgroup start twice as
+    // many (1-4 % at D = 128, 2-12 % at D = 160; level at D = 64 and 96)
+    if (D >= 128 && S <= 256 && (long long)BH * ((S + 127) / 128) < 256) *tm = 64;
+    // many short heads under the mask at D = 96 and 160 (S = 512, 1024; four 128-row workgroups per CU and more):
+    // the 64 x 32 tile, which cuts the diagonal finest, is 4-7 % ahead
+    if (causal && (D == 96 || D == 160) && S >= 512 && S <= 1024 && (long long)BH * ((S + 127) / 128) >= 1024) {
+        *tm = 64;
+        *tn = 32;
+    }
     // 256 query rows per workgroup (eight wavefronts share every K/V tile: half the tile loads per MFMA; one
-    // workgroup per CU) win from D = 96 upward once they give every CU a workgroup: 3 % at D = 96 and 128,
-    // 5-8 % at D = 160 (whose 128-row query tile has to take 32-row K/V tiles to keep two workgroups on a CU).
+    // workgroup per CU) win from D = 96 upward once they give every CU a workgroup and the sequence is long
+    // enough: 2-3 % at D = 96 from S = 4096 (level at 2048, 6 % behind there with 256 heads), 3 % at D = 128
+    // from S = 2048, 1-2.5 % over 128 x 64 at D = 160 from S = 1024.
     // Not under the causal mask (a workgroup's diagonal band is four masked tiles instead of two and the query
-    // tiles of a head balance worse: within 2 % either way at S = 8192 and 16384, 13-25 % slower at S = 2048, up to
-    // 2.7 times at D = 160, whose masked 64-row step spills), not at D = 64 (3-14 % slower).
+    // tiles of a head balance worse: within 2 % either way at S = 8192 and 16384, 5-25 % slower at S = 2048),
+    // not at D = 64 (3-14 % slower).
     const long long wg256 = (long long)BH * ((S + 255) / 256);
-    const bool wide = !causal && D >= 96 && wg256 >= 256 && S >= (D == 160 ? 1024 : 2048);
+    bool wide = !causal && D >= 96 && wg256 >= 256 && S >= (D == 160 ? 1024 : D == 96 ? 4096 : 2048);
+    // (D = 160 below S = 4096: ahead while a CU gets up to three such workgroups, 3-4 % behind 128 x 64 with more)
+    if (D == 160 && S < 4096 && wg256 >= 1024) wide = false;
     if (wide) {
         *tm = 256;
         *tn = 64;
@@ -142,8 +157,13 @@ bool valid_tile_kv(int tm, int tn, bool paged)
 
 void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
 {
+    // (decoding shapes are bound by the cache read, not by the loop)
     *tm = Sq <= 64 ? 64 : 128;
-    *tn = (Skv >= 512 && D != 160) ? 64 : 32;   // decoding shapes are bound by the cache read, not by the loop
+    *tn = Skv >= 512 ? 64 : 32;
+    // D = 160: 32-row tiles are level or ahead (3-10 %) until the query block is long (2048 rows: 64-row tiles
+    // 2-5 % ahead); D = 96: a handful of query rows per key/value head read the cache 2-15 % faster in 32-row tiles
+    if (D == 160) *tn = Sq >= 2048 ? 64 : 32;
+    if (D == 96 && Sq <= 16) *tn = 32;
 }
 
 }  // namespace
@@ -414,7 +434,7 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
     // square problem, under the same conditions (with 256 such workgroups the 128-row tile has 512 and is not
     // split either, so the split count does not depend on this choice)
     if (heuristic_tile && splits == 1 && block_table == nullptr && kv_lens == nullptr &&
-        !(flags & TSDPA_FLAG_CAUSAL) && D >= 96 && rows >= (D == 160 ? 1024 : 2048) &&
+        !(flags & TSDPA_FLAG_CAUSAL) && D >= 96 && rows >= (D == 160 ? 1024 : D == 96 ? 4096 : 2048) &&
         (int64_t)B * Hkv * ((rows + 255) / 256) >= 256) {
         tile_m = 256;
         tile_n = 64;

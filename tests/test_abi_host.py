@@ -307,6 +307,13 @@ def test_default_tile_is_a_legal_tile(lib):
     assert binding.default_tile(2, 32, 8192, 160, binding.BF16) == (256, 64)
     assert binding.default_tile(2, 32, 8192, 64, binding.BF16) == (128, 64)
     assert binding.default_tile(1, 8, 4096, 128, binding.BF16) == (128, 64)     # 128 workgroups of 256 rows: too few
+    # D = 96 takes it from S = 4096; D = 160 runs 64-row K/V tiles from S = 512 and 64 query rows on a few short heads
+    assert binding.default_tile(4, 16, 2048, 96, binding.BF16) == (128, 64)
+    assert binding.default_tile(4, 16, 4096, 96, binding.BF16) == (256, 64)
+    assert binding.default_tile(2, 32, 8192, 160, binding.BF16, binding.FLAG_CAUSAL) == (128, 64)
+    assert binding.default_tile(1, 16, 1024, 160, binding.BF16) == (128, 64)
+    assert binding.default_tile(4, 16, 197, 160, binding.BF16) == (64, 32)
+    assert binding.default_tile(16, 16, 197, 160, binding.BF16) == (128, 32)
     assert len(binding.TILE_ORDER) == 7
     with pytest.raises(binding.TiledSdpaError):
         binding.default_tile(1, 1, 16, 72, 0)

@@ -69,7 +69,8 @@ def test_main_loop_of_the_headline_kernels_touches_no_scratch_memory(dtype, tmp_
 
     kernels = {}
     # 32-row and 64-row K/V tiles are separate translation units, each with the flags the build gives it
-    for src in (CSRC / f"sdpa_fwd_{dtype}_d128.hip", CSRC / f"sdpa_fwd_{dtype}_d128_tn64.hip"):
+    for src in (CSRC / f"sdpa_fwd_{dtype}_d128.hip", CSRC / f"sdpa_fwd_{dtype}_d128_tn64.hip",
+                CSRC / f"sdpa_fwd_{dtype}_d160_tn64.hip"):
         asm = tmp_path / (src.stem + ".s")
         cmd = [HIPCC, *lib_build.FLAGS, *lib_build.extra_flags(src), "-S", "--cuda-device-only",
                str(src), "-o", str(asm)]
@@ -85,6 +86,15 @@ def test_main_loop_of_the_headline_kernels_touches_no_scratch_memory(dtype, tmp_
         n = scratch_ops_in_main_loop(lines)
         assert n == 0, f"{name}: {n} scratch accesses inside the main loop (T_M = {32 * int(m.group(1))}, T_N = {m.group(2)})"
     assert checked == 4, f"expected the 128x32, 128x64, 128x128 and 256x64 instantiations, found {checked}"
+    # D = 160 on 64-row K/V tiles (the heuristic's tiles there from S = 512): no scratch access in the main loop
+    checked = 0
+    for name, lines in kernels.items():
+        m = re.search(r"Li160ELi(4|8)ELi64ELi\dELi0E", name)
+        if m:
+            checked += 1
+            n = scratch_ops_in_main_loop(lines)
+            assert n == 0, f"{name}: {n} scratch accesses inside the main loop (D = 160, T_M = {32 * int(m.group(1))})"
+    assert checked == 2, f"expected the 128x64 and 256x64 instantiations at D = 160, found {checked}"
     # every instantiation has two loops with MFMAs (unmasked tiles, masked tiles) and, in the square problem, at
     # most one without (wavefronts past the end of a ragged sequence): a buffer descriptor the compiler takes for
     # lane-dependent turns each of its loads into a loop over distinct descriptors (this happened to the
