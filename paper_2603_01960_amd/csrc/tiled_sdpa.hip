@@ -155,14 +155,15 @@ bool valid_tile_kv(int tm, int tn, bool paged)
     return (tm == 64 || tm == 128) && (tn == 32 || tn == 64);
 }
 
-void pick_tile_kv(int Sq, int Skv, int D, int *tm, int *tn)
+void pick_tile_kv(long long heads, int Sq, int Skv, int D, int *tm, int *tn)
 {
     // (decoding shapes are bound by the cache read, not by the loop)
     *tm = Sq <= 64 ? 64 : 128;
     *tn = Skv >= 512 ? 64 : 32;
     // D = 160: 32-row tiles are level or ahead (3-10 %) until the query block is long (2048 rows: 64-row tiles
-    // 2-5 % ahead); D = 96: a handful of query rows per key/value head read the cache 2-15 % faster in 32-row tiles
-    if (D == 160) *tn = Sq >= 2048 ? 64 : 32;
+    // 2-5 % ahead) or its 128-row tiles are fewer than the CUs (15 % ahead at one head's 512 or 1024 rows);
+    // D = 96: a handful of query rows per key/value head read the cache 2-15 % faster in 32-row tiles
+    if (D == 160) *tn = (Sq >= 2048 || (Sq >= 128 && Skv >= 512 && heads * ((Sq + 127) / 128) < 256)) ? 64 : 32;
     if (D == 96 && Sq <= 16) *tn = 32;
 }
 
@@ -316,7 +317,7 @@ int tiled_sdpa_kv_default_splits(int B, int H, int Sq, int Skv, int D, int dtype
     const int st = validate_shape_kv(B, H, Sq, Skv, D, dtype, flags);
     if (st != TSDPA_OK) return st;
     int tm, tn;
-    pick_tile_kv(Sq, Skv, D, &tm, &tn);
+    pick_tile_kv((long long)B * H, Sq, Skv, D, &tm, &tn);
     *splits = pick_splits(B * H, Sq, Skv, tm, tn);
     return TSDPA_OK;
 }
@@ -362,7 +363,7 @@ int tiled_sdpa_fwd_kvcache_static(const void *q, const void *k, const void *v, v
     if ((int64_t)(H / Hkv) * Sq > (int64_t)std::numeric_limits<int>::max()) return TSDPA_ERR_BAD_SHAPE;
     if (splits == 0) {
         int tm = tile_m, tn = tile_n;
-        if (tm == 0 && tn == 0) pick_tile_kv((H / Hkv) * Sq, Skv, D, &tm, &tn);
+        if (tm == 0 && tn == 0) pick_tile_kv((long long)B * Hkv, (H / Hkv) * Sq, Skv, D, &tm, &tn);
         else if (!valid_tile_kv(tm, tn, false)) return TSDPA_ERR_BAD_TILE;
         splits = pick_splits(B * Hkv, (H / Hkv) * Sq, Skv, tm, tn);
     }
@@ -423,7 +424,7 @@ static int fwd_kv_impl(const void *q, const void *k, const void *v, void *o, flo
     if ((bits & 15u) != 0 || (((uintptr_t)lse | (uintptr_t)kv_lens) & 3u) != 0) return TSDPA_ERR_MISALIGNED;
     const bool heuristic_tile = tile_m == 0 && tile_n == 0;
     if (heuristic_tile)
-        pick_tile_kv(rows, Skv, D, &tile_m, &tile_n);
+        pick_tile_kv((long long)B * Hkv, rows, Skv, D, &tile_m, &tile_n);
     else if (!valid_tile_kv(tile_m, tile_n, block_table != nullptr))
         return TSDPA_ERR_BAD_TILE;
     if (std::isnan(scale)) scale = 1.0f / std::sqrt((float)D);
