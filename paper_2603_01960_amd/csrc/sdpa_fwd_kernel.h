@@ -164,10 +164,10 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     constexpr int TM = NW * 32;
     constexpr bool COMPACT = G::COMPACT;
     constexpr int CPR = G::ROW / 16;              // 16-byte chunks per LDS row
-    constexpr int GCPR = D / 8;                   // ... of which this many hold data
+    constexpr int GCPR = D / 8;                   // (all of them hold data; the rows of the output transpose may be longer)
     // A direct-to-LDS load instruction fills one unit: 64 consecutive chunks (1 KiB) of a tile slot.
     constexpr int U = TN * CPR / 64;              // units per K or V tile
-    constexpr int NLD = U / NW;                   // padded rows: units of a tensor's tile per wavefront
+    constexpr int NLD = U / NW;                   // units of one tensor's tile per wavefront (where that divides)
     constexpr int L = 2 * U / NW;                 // load instructions per wavefront per K/V tile pair
     static_assert((TN * CPR) % 64 == 0 && L >= 1 && (2 * U) % NW == 0, "tile pair does not divide over the workgroup");
     static_assert(COMPACT || U % NW == 0, "tile does not divide over the workgroup");
@@ -257,8 +257,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
     // that range and therefore fetches the global chunk that the swizzle maps to position p.
     const auto k_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(k + kv_off), (short)0, Skv * G::GROW, 0x00020000);
     const auto v_rsrc = __builtin_amdgcn_make_buffer_rsrc((void *)(v + kv_off), (short)0, Skv * G::GROW, 0x00020000);
-    constexpr int kNoFetch = 0x60000000;          // beyond any descriptor (one head holds < 2^30 bytes)
-    // Padded rows.  The swizzles repeat every 16 rows and a load instruction of the workgroup's sweep lands
+    // Rows of a power of two.  The swizzles repeat every 16 rows and a load instruction of the workgroup's sweep lands
     // NW * RPI rows after the previous one, so the per-lane offsets repeat with period NG in `it`: only NG of them are
     // kept in vector registers, the rest of the distance travels in the scalar offset.
     constexpr int RPI = COMPACT ? 1 : 64 / CPR;   // tile rows filled by one load instruction
@@ -273,8 +272,8 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
             const int p = (it * NW + wave) * 64 + lane;
             const int r = p / CPR, cp = p % CPR;
             const int kc = cp ^ G::kswz(r), vc = cp ^ (G::vswz(r) << 2);   // global chunk that belongs at LDS chunk cp
-            k_goff[it] = kc < GCPR ? r * G::GROW + (kc << 4) : kNoFetch;
-            v_goff[it] = vc < GCPR ? r * G::GROW + (vc << 4) : kNoFetch;
+            k_goff[it] = r * G::GROW + (kc << 4);
+            v_goff[it] = r * G::GROW + (vc << 4);
         }
     }
     // Compact rows.  The units of a tile pair, K's U then V's U, are dealt round-robin: load i of this wavefront is
@@ -341,7 +340,7 @@ sdpa_fwd_kernel(const T *__restrict__ q, const T *__restrict__ k, const T *__res
         }
         return TileSrc{rsrc, soff};
     };
-    // load instruction `it` (of NLD) of a tile in padded rows
+    // load instruction `it` (of NLD) of a tile in rows of a power of two
     auto load_part = [&](const TileSrc &src, const int (&goff)[NG], lds_ptr dst, int it) __attribute__((always_inline)) {
         __builtin_amdgcn_raw_ptr_buffer_load_lds(src.rsrc, (TSDPA_LDS void *)(dst + (it * NW + wave) * 1024), 16,
                                                  goff[it % NG], src.soff + (it / NG) * GSTEP, 0, 0);
