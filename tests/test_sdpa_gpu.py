@@ -309,6 +309,21 @@ def test_head_dims_96_and_160_mid_size_default_tile_and_guards(D):
     assert np.abs(o.cpu().double().numpy() - ref).max() <= TOL["f16"]
 
 
+@pytest.mark.parametrize("D", [96, 160])
+def test_head_dims_96_and_160_long_sequences_sampled_rows(D):
+    """S = 8192 (the longest length of the grid of Section 4.3) on the tiles the heuristic takes there: the
+    256-row query tile without the mask, 128 x 64 under it; rows on both sides of every tile edge plus a stride."""
+    B, H, S = 1, 8, 8192
+    dtype = "bf16" if D == 160 else "f16"
+    q, k, v = make_qkv(B, H, S, D, dtype, seed=9800 + D)
+    assert binding.default_tile(B, H, S, D, binding.BF16) == (256, 64)
+    assert binding.default_tile(B, H, S, D, binding.BF16, binding.FLAG_CAUSAL) == (128, 64)
+    rows = sample_rows(S, limit=8)
+    check(q, k, v, dtype, rows=rows, tag=f"D={D} S={S} sampled rows")
+    check(q, k, v, dtype, rows=rows, causal=True, tag=f"D={D} S={S} causal, sampled rows")
+    check(q, k, v, dtype, rows=rows, tile=(128, 32), tag=f"D={D} S={S} sampled rows")
+
+
 # ------------------------------------------------------------------ causal mask (Section 4.1.3)
 @pytest.mark.parametrize("tile", TILES)
 @pytest.mark.parametrize("dtype,D", [("f16", 64), ("bf16", 128), ("bf16", 64), ("f16", 128)])
